@@ -1,0 +1,128 @@
+/*
+ * fa_mi355 -- exact fused scaled-dot-product attention for AMD MI355X (gfx950).
+ *
+ * C ABI of libfa_mi355.so.  The operation is the one stated in section 2.1 of the
+ * FlashAttention-3 paper (arXiv 2407.08608):
+ *
+ *     S = scale * Q K^T,   P = softmax_rows(S [causal: keys j > i masked]),   O = P V,
+ *
+ * computed per (batch, head) without ever materialising S or P (Algorithm 1: tiled
+ * Q K^T, online softmax with running row maximum / row sum, P V accumulated on chip),
+ * and the row-wise logsumexp  L_i = m_i + log(l_i)  written out for the backward pass.
+ *
+ * Conventions for every entry point
+ *   - All tensor arguments are DEVICE pointers owned by the caller.  The library reads
+ *     inputs, writes outputs, and keeps no reference after the call returns.
+ *   - Tensors are contiguous [B, H, N, d] with d fastest (paper section 3.3: inputs are
+ *     contiguous in the head dimension); lse / D-like vectors are fp32 [B, H, N].
+ *     Every tensor pointer must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous with respect to the host: they enqueue kernels and return.  They
+ *     never synchronise, allocate or free device memory, throw, or abort.
+ *   - The return value is an fa_status.  On any status other than FA_OK nothing has
+ *     been launched by that call.  fa_status_string() names a status.
+ *   - Supported head dimensions: d in {64, 128, 256}.  N >= 1 (any N; rows past N are
+ *     never read or written).  B, H >= 1.  scale finite and > 0.  causal in {0, 1};
+ *     causal means key j is visible to query i iff j <= i (N_q == N_k).
+ *   - Thread-safe: no mutable global state.
+ */
+#ifndef FA_MI355_H
+#define FA_MI355_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FA_OK = 0,
+    FA_ERR_NULL = 1,        /* a required pointer is NULL */
+    FA_ERR_SHAPE = 2,       /* B, H, N or block_rows not positive, scale not finite/positive, causal not 0/1 */
+    FA_ERR_DTYPE = 3,       /* dtype is not a member of fa_dtype */
+    FA_ERR_UNSUPPORTED = 4, /* a valid request this build has no kernel for (e.g. head dim 96) */
+    FA_ERR_ALIGN = 5,       /* a tensor pointer is not 16-byte aligned */
+    FA_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than fa_bwd_workspace_bytes() */
+    FA_ERR_LAUNCH = 7       /* the HIP runtime rejected a launch */
+} fa_status;
+
+typedef enum {
+    FA_F32 = 0,     /* fp32 in / fp32 out, fp32 arithmetic (d = 64 only) */
+    FA_BF16 = 1,    /* bf16 in / bf16 out, fp32 accumulate */
+    FA_F16 = 2,     /* fp16 in / fp16 out, fp32 accumulate */
+    FA_FP8_E4M3 = 3 /* OCP e4m3 ("fn") codes in, bf16 out, fp32 accumulate */
+} fa_dtype;
+
+/*
+ * Forward pass (section 2.1; Algorithms 1 and 2).
+ *   q, k, v : [B,H,N,d] of `dtype`            (device, read)
+ *   o       : [B,H,N,d] of `dtype` (bf16 when dtype == FA_FP8_E4M3)   (device, written)
+ *   lse     : fp32 [B,H,N], natural log of sum_j exp(scale * q_i . k_j) over visible j
+ *             (device, written)
+ * With dtype == FA_FP8_E4M3 the codes are taken at unit scale (the block-scaled path is
+ * fa_fwd_fp8).  FA_F32 supports d = 64 only.
+ */
+int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
+           int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
+
+/*
+ * FP8 forward with per-block scales (section 3.3, "block quantization": one scalar per
+ * block of rows of Q, K and V; each block of S is rescaled by the product of its Q-block
+ * and K-block scales at no extra cost).
+ *   q8, k8, v8 : e4m3 codes [B,H,N,d]                         (device, read)
+ *   q_scale, k_scale, v_scale : fp32 [B,H,ceil(N/block_rows)]; the real tensor is
+ *             code * scale of its block                        (device, read)
+ *   o   : bf16 [B,H,N,d]; lse : fp32 [B,H,N]                   (device, written)
+ *   block_rows : rows per quantisation block; must be 128.
+ * Q and K are expected to have been multiplied by the same orthogonal matrix
+ * ("incoherent processing"); the kernel neither knows nor cares, since (QM)(KM)^T = QK^T.
+ */
+int fa_fwd_fp8(const void* q8, const void* k8, const void* v8,
+               const float* q_scale, const float* k_scale, const float* v_scale,
+               void* o, float* lse, int B, int H, int N, int d, int block_rows,
+               float scale, int causal, void* stream);
+
+/*
+ * Quantisation pre-pass (section 3.3: block quantization + incoherent processing).
+ * Row-wise  y = (x * signs) H_d / sqrt(d)  with H_d the Sylvester Hadamard matrix
+ * (skipped when signs == NULL), then per block of `block_rows` rows of one head:
+ *     scale = amax|y| / 448  (1 if the block is all zero),
+ *     code  = round-to-nearest-even e4m3 of clamp(y * (448 / amax), +-448).
+ *   x       : [B,H,N,d] of in_dtype (FA_F32, FA_BF16 or FA_F16)   (device, read)
+ *   x8      : e4m3 codes [B,H,N,d]                                (device, written)
+ *   scales  : fp32 [B,H,ceil(N/block_rows)]                        (device, written)
+ *   signs   : int8 [d] of +1 / -1, or NULL for no transform        (device, read)
+ *   per_tensor : 0 = per-block scales; 1 = one scale from the amax of the whole
+ *             transformed tensor, replicated into every slot of `scales` (the per-tensor
+ *             baseline of section 4.3).  In this mode `scales` is also used as scratch
+ *             during the call.
+ *   block_rows must be 128.
+ */
+int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales,
+                          int B, int H, int N, int d, int block_rows,
+                          const signed char* signs, int per_tensor, void* stream);
+
+/*
+ * Backward pass (section 2.1 chain rule; Algorithm 3):
+ *     D = rowsum(dO o O);  P = exp(S - L);  dV = P^T dO;  dP = dO V^T;
+ *     dS = P o (dP - D);   dQ = scale * dS K;   dK = scale * dS^T Q.
+ *   q, k, v, o, dout : [B,H,N,d] of `dtype`; lse : fp32 [B,H,N] from fa_fwd   (device, read)
+ *   dq, dk, dv       : [B,H,N,d] of `dtype`                                   (device, written)
+ *   workspace        : device scratch of at least fa_bwd_workspace_bytes(...) bytes,
+ *                      16-byte aligned, owned by the caller, contents undefined on return.
+ * dtype FA_BF16 or FA_F16; d = 128 only (others: FA_ERR_UNSUPPORTED).  dQ is accumulated
+ * with fp32 atomics, so its low-order bits may differ from run to run.
+ */
+size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype);
+
+int fa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
+           const void* dout, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+           int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
+
+/* Static, NUL-terminated description of an fa_status value. */
+const char* fa_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FA_MI355_H */

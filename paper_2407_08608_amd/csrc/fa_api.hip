@@ -1,0 +1,106 @@
+// C ABI of libfa_mi355.so: argument validation and dispatch.  See include/fa_mi355.h for the
+// contract of every entry point.
+#include <math.h>
+#include <stdint.h>
+
+#include "fa_launch.h"
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool head_dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
+
+int check_common(int B, int H, int N, int d, float scale, int causal) {
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return FA_ERR_SHAPE;
+    if (!(scale > 0.f) || !isfinite(scale)) return FA_ERR_SHAPE;
+    if (causal != 0 && causal != 1) return FA_ERR_SHAPE;
+    if ((long)B * H * N > 0x7fffffffL) return FA_ERR_SHAPE;
+    if (!head_dim_ok(d)) return FA_ERR_UNSUPPORTED;
+    return FA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* fa_status_string(int status) {
+    switch (status) {
+        case FA_OK: return "ok";
+        case FA_ERR_NULL: return "a required pointer is NULL";
+        case FA_ERR_SHAPE: return "invalid shape, scale or flag";
+        case FA_ERR_DTYPE: return "unknown dtype";
+        case FA_ERR_UNSUPPORTED: return "valid request with no kernel in this build";
+        case FA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+        case FA_ERR_WORKSPACE: return "workspace missing or too small";
+        case FA_ERR_LAUNCH: return "HIP runtime rejected the launch";
+        default: return "unknown status";
+    }
+}
+
+int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, float scale,
+           int causal, int dtype, void* stream) {
+    if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
+    if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
+    int st = check_common(B, H, N, d, scale, causal);
+    if (st != FA_OK) return st;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dtype) {
+        case FA_F32: return fa::launch_fwd_f32(q, k, v, o, lse, B, H, N, d, scale, causal, s);
+        case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, N, d, scale, causal, s);
+        case FA_F16: return fa::launch_fwd_f16(q, k, v, o, lse, B, H, N, d, scale, causal, s);
+        default: return fa::launch_fwd_fp8(q, k, v, nullptr, nullptr, nullptr, o, lse, B, H, N, d, scale, causal, s);
+    }
+}
+
+int fa_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
+               const float* v_scale, void* o, float* lse, int B, int H, int N, int d, int block_rows, float scale,
+               int causal, void* stream) {
+    if (!q8 || !k8 || !v8 || !q_scale || !k_scale || !v_scale || !o || !lse) return FA_ERR_NULL;
+    int st = check_common(B, H, N, d, scale, causal);
+    if (st != FA_OK) return st;
+    if (block_rows <= 0) return FA_ERR_SHAPE;
+    if (block_rows != 128) return FA_ERR_UNSUPPORTED;
+    if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
+    return fa::launch_fwd_fp8(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, d, scale, causal,
+                              static_cast<hipStream_t>(stream));
+}
+
+int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales, int B, int H, int N, int d,
+                          int block_rows, const signed char* signs, int per_tensor, void* stream) {
+    if (!x || !x8 || !scales) return FA_ERR_NULL;
+    if (in_dtype < FA_F32 || in_dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
+    if (in_dtype == FA_FP8_E4M3) return FA_ERR_UNSUPPORTED;
+    if (B <= 0 || H <= 0 || N <= 0 || d <= 0 || block_rows <= 0) return FA_ERR_SHAPE;
+    if (per_tensor != 0 && per_tensor != 1) return FA_ERR_SHAPE;
+    if ((long)B * H * N > 0x7fffffffL) return FA_ERR_SHAPE;
+    if (!head_dim_ok(d) || block_rows != 128) return FA_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(x8)) return FA_ERR_ALIGN;
+    return fa::launch_quant_hadamard(x, in_dtype, x8, scales, B, H, N, d, signs, per_tensor,
+                                     static_cast<hipStream_t>(stream));
+}
+
+size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype) {
+    if (B <= 0 || H <= 0 || N <= 0 || d != 128) return 0;
+    if (dtype != FA_BF16 && dtype != FA_F16) return 0;
+    return fa::bwd_workspace_bytes(B, H, N, d);
+}
+
+int fa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout, void* dq,
+           void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, float scale,
+           int causal, int dtype, void* stream) {
+    if (!q || !k || !v || !o || !lse || !dout || !dq || !dk || !dv) return FA_ERR_NULL;
+    if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
+    int st = check_common(B, H, N, d, scale, causal);
+    if (st != FA_OK) return st;
+    if (d != 128 || (dtype != FA_BF16 && dtype != FA_F16)) return FA_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dout) ||
+        !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
+        return FA_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fa::bwd_workspace_bytes(B, H, N, d)) return FA_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return FA_ERR_ALIGN;
+    return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, N, d, scale, causal, dtype,
+                          static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,122 @@
+// Device-side building blocks shared by the attention kernels: vector types, MFMA
+// wrappers for gfx950, the transposing LDS reads, and wavefront helpers.
+//
+// Register layouts used throughout (64-lane wavefront, lane l, col = l % 32, half = l / 32):
+//   v_mfma_f32_32x32x16_{bf16,f16}: an A (or B) operand lane holds row (col) `l % 32` and the
+//     8 contraction indices 8*half .. 8*half+7; the fp32 result lane holds column `l % 32`
+//     and, in register r of 16, row 8*(r/4) + 4*half + r%4.
+// Computing the transposed score tile S^T = K Q^T therefore leaves one query per lane
+// column with its keys spread over the lane's own registers, and those registers, packed
+// to 16 bits, are already a valid B operand for O^T = V^T P^T as long as the V operand
+// enumerates keys in the same order -- the gfx950 counterpart of the accumulator-to-operand
+// register permutation of the paper's section 3.3 (FP8 layout discussion).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fa {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(2))) int i32x2;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+
+struct bf16_tag {};
+struct f16_tag {};
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <typename Tag> struct Elem;
+
+template <> struct Elem<bf16_tag> {
+    // D = A(32x16) * B(16x32) + C, 16-bit operands packed 8 per lane in a 128-bit carrier
+    static __device__ __forceinline__ f32x16 mma(i32x4 a, i32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                       __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int pack2(float lo, float hi) {  // RNE
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(int, __builtin_convertvector(v, bf16x2));
+    }
+    static __device__ __forceinline__ float to_float(uint16_t bits) {
+        return __builtin_bit_cast(float, (uint32_t)bits << 16);
+    }
+};
+
+template <> struct Elem<f16_tag> {
+    static __device__ __forceinline__ f32x16 mma(i32x4 a, i32x4 b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                      __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int pack2(float lo, float hi) {  // RNE
+        f32x2 v = {lo, hi};
+        return __builtin_bit_cast(int, __builtin_convertvector(v, f16x2));
+    }
+    static __device__ __forceinline__ float to_float(uint16_t bits) {
+        return (float)__builtin_bit_cast(_Float16, bits);
+    }
+};
+
+// ds_read_b64_tr_b16: the 16 lanes of a group each point at 4 consecutive 16-bit elements;
+// seen as a 4x16 matrix (row r = what lanes 4r..4r+3 point at), lane i of the group
+// receives column i.  Used to read a [key][d] tile as the key-contiguous MFMA operand.
+static __device__ __forceinline__ i32x2 lds_read_tr16(const void* lds_ptr) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_vec_ptr;
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_vec_ptr)(uintptr_t)lds_ptr);
+    return __builtin_bit_cast(i32x2, v);
+}
+
+// ds_read_b64_tr_b8: same with bytes; the group's data is an 8x16 byte matrix (row r = what
+// lanes 2r, 2r+1 point at) and lane i receives column i.
+static __device__ __forceinline__ i32x2 lds_read_tr8(const void* lds_ptr) {
+    typedef i32x2 __attribute__((address_space(3))) * lds_vec_ptr;
+    return __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_vec_ptr)(uintptr_t)lds_ptr);
+}
+
+// v_permlane32_swap exchanges the upper half of its first register with the lower half of
+// its second.  Fed two copies of x it yields (x of lanes 0..31 replicated, x of lanes 32..63
+// replicated).  The second copy is laundered through an empty asm so the compiler cannot
+// treat the two results as one value.
+struct HalfPair {
+    float lo, hi;  // value of lane (l % 32), value of lane (l % 32) + 32
+};
+static __device__ __forceinline__ HalfPair both_halves(float x) {
+    uint32_t a = __builtin_bit_cast(uint32_t, x);
+    uint32_t b = a;
+    asm volatile("" : "+v"(b));
+    auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+    uint32_t r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    return {__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+
+static __device__ __forceinline__ float max_both_halves(float x) {
+    HalfPair p = both_halves(x);
+    return fmaxf(p.lo, p.hi);
+}
+
+static __device__ __forceinline__ float sum_both_halves(float x) {
+    HalfPair p = both_halves(x);
+    return p.lo + p.hi;
+}
+
+static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// The chip deals consecutive workgroup ids round-robin to its 8 XCDs, each with a private
+// L2.  Remap a linear id so that ids landing on one XCD cover a contiguous range of work
+// items (all query tiles of a head share that head's K and V in one L2).
+static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
+    constexpr int kXcd = 8;
+    if (total % kXcd != 0) return id;
+    return (id % kXcd) * (total / kXcd) + id / kXcd;
+}
+
+}  // namespace fa

@@ -1,0 +1,385 @@
+// Forward attention kernels for gfx950: 16-bit (bf16 / fp16) MFMA path and the fp32 path.
+//
+// One workgroup owns a tile of BR = NW * 32 * RQ query rows of one (batch, head) and walks
+// the key/value blocks of that head (paper Algorithm 1: T_r query tiles on the grid, T_c
+// key blocks in the inner loop).  Per block: S^T = K_j Q_i^T on MFMA, online softmax with
+// running row maximum m and row sum l, O^T += V_j^T P^T on MFMA, O rescaled by
+// exp(m_old - m_new); epilogue O / l and L = m + log l.  K_j and V_j are staged through a
+// double-buffered LDS ring that the next block's global loads fill while the current block
+// is being computed (the role the producer warpgroup plays in the paper).
+#include "fa_device.h"
+#include "fa_launch.h"
+
+namespace fa {
+
+template <int D, int BC, int NT>
+struct TileCopy {
+    static constexpr int kChunksPerRow = D / 8;  // 16-byte chunks of 8 16-bit elements
+    static constexpr int kChunks = BC * kChunksPerRow;
+    static constexpr int kPerThread = kChunks / NT;
+    static_assert(kChunks % NT == 0, "tile must divide evenly over the workgroup");
+
+    // rows past N read as zero so that masked probabilities multiply finite values
+    static __device__ __forceinline__ void from_global(const uint16_t* head, int key0, int N, int tid,
+                                                       i32x4 (&regs)[kPerThread]) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            int c = tid + i * NT;
+            int row = c / kChunksPerRow, col = c % kChunksPerRow;
+            int key = key0 + row;
+            i32x4 z = {0, 0, 0, 0};
+            regs[i] = key < N ? *reinterpret_cast<const i32x4*>(head + (size_t)key * D + col * 8) : z;
+        }
+    }
+    template <int STRIDE>
+    static __device__ __forceinline__ void to_lds(uint16_t* lds, int tid, const i32x4 (&regs)[kPerThread]) {
+#pragma unroll
+        for (int i = 0; i < kPerThread; ++i) {
+            int c = tid + i * NT;
+            int row = c / kChunksPerRow, col = c % kChunksPerRow;
+            *reinterpret_cast<i32x4*>(lds + row * STRIDE + col * 8) = regs[i];
+        }
+    }
+};
+
+template <typename Tag, int D, int BC, int NW, int RQ, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, (RQ == 1 && D <= 128) ? 2 : 1)
+fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                    const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
+                    int N, int n_qtiles, int total_wg, float scale) {
+    constexpr int NT = NW * 64;
+    constexpr int BR = NW * 32 * RQ;
+    constexpr int KSTR = D + 8;   // +16 B per row: 128-bit row reads hit distinct banks
+    constexpr int VSTR = D + 32;  // +64 B per row: the 4-row transposing reads hit distinct banks
+    constexpr int KT = BC / 32;   // 32-key score tiles per block
+    constexpr int KS = D / 16;    // MFMA steps along the head dimension
+    constexpr int DT = D / 32;    // 32-column output tiles
+    constexpr int SL = BC / 16;   // 16-key MFMA steps along the keys
+    using E = Elem<Tag>;
+    using Copy = TileCopy<D, BC, NT>;
+
+    __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][BC * KSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][BC * VSTR];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int bh = id / n_qtiles;
+    int qt = id % n_qtiles;
+    if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint16_t* qh = q + head_off;
+    const uint16_t* kh = k + head_off;
+    const uint16_t* vh = v + head_off;
+
+    const int wave_q0 = qt * BR + wave * (32 * RQ);
+    const float sc = scale * kLog2e;  // exp(scale*s - scale*m) = exp2(sc*s - sc*m)
+
+    // Q_i^T as the B operand, resident in registers for the whole loop
+    i32x4 qreg[RQ][KS];
+#pragma unroll
+    for (int rq = 0; rq < RQ; ++rq) {
+        int row = wave_q0 + rq * 32 + col;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            i32x4 z = {0, 0, 0, 0};
+            qreg[rq][ks] = row < N ? *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8) : z;
+        }
+    }
+
+    f32x16 oacc[RQ][DT];
+    float m_run[RQ], l_run[RQ];
+#pragma unroll
+    for (int rq = 0; rq < RQ; ++rq) {
+        m_run[rq] = -INFINITY;
+        l_run[rq] = 0.f;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[rq][dt][r] = 0.f;
+    }
+
+    // key blocks this workgroup must visit
+    int last_q = min(qt * BR + BR, N) - 1;
+    int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+
+    i32x4 kpre[Copy::kPerThread], vpre[Copy::kPerThread];
+    Copy::from_global(kh, 0, N, tid, kpre);
+    Copy::from_global(vh, 0, N, tid, vpre);
+    Copy::template to_lds<KSTR>(lds_k[0], tid, kpre);
+    Copy::template to_lds<VSTR>(lds_v[0], tid, vpre);
+    __syncthreads();
+
+    // transposing V read: lane -> (row within a 4-key group, 4-column chunk) of its 16-lane group
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+    for (int t = 0; t < n_blocks; ++t) {
+        const int st = t & 1;
+        const int key0 = t * BC;
+        const bool more = (t + 1 < n_blocks);
+        if (more) {
+            Copy::from_global(kh, key0 + BC, N, tid, kpre);
+            Copy::from_global(vh, key0 + BC, N, tid, vpre);
+        }
+
+        // a wave whose queries all precede this block has nothing to add (causal)
+        const bool wave_active = !CAUSAL || key0 <= wave_q0 + 32 * RQ - 1;
+        if (wave_active) {
+            // ---- GEMM0: S^T = K_j Q_i^T
+            f32x16 sacc[RQ][KT];
+#pragma unroll
+            for (int rq = 0; rq < RQ; ++rq)
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) sacc[rq][kt][r] = 0.f;
+            const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    i32x4 a = *reinterpret_cast<const i32x4*>(ks_base + kt * 32 * KSTR + ks * 16);
+#pragma unroll
+                    for (int rq = 0; rq < RQ; ++rq) sacc[rq][kt] = E::mma(a, qreg[rq][ks], sacc[rq][kt]);
+                }
+            }
+
+            // ---- mask: keys past N, and keys after the query when causal
+            const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
+            if (need_mask) {
+#pragma unroll
+                for (int rq = 0; rq < RQ; ++rq) {
+                    int qi = wave_q0 + rq * 32 + col;
+                    int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) {
+                            int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                            if (key > limit) sacc[rq][kt][r] = -INFINITY;
+                        }
+                }
+            }
+
+            // ---- online softmax (Algorithm 1: m, P~, l) and the operand for GEMM1
+            i32x4 pb[RQ][SL];
+#pragma unroll
+            for (int rq = 0; rq < RQ; ++rq) {
+                float mx = sacc[rq][0][0];
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[rq][kt][r]);
+                mx = max_both_halves(mx);
+                float m_new = fmaxf(m_run[rq], mx);
+                float corr = fast_exp2((m_run[rq] - m_new) * sc);
+                m_run[rq] = m_new;
+                float mb = m_new * sc;
+                float psum = 0.f;
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    float p[16];
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        p[r] = fast_exp2(__builtin_fmaf(sacc[rq][kt][r], sc, -mb));
+                        psum += p[r];
+                    }
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        i32x4 w;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) w[e] = E::pack2(p[8 * s2 + 2 * e], p[8 * s2 + 2 * e + 1]);
+                        pb[rq][2 * kt + s2] = w;
+                    }
+                }
+                l_run[rq] = l_run[rq] * corr + psum;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[rq][dt][r] *= corr;
+            }
+
+            // ---- GEMM1: O^T += V_j^T P^T
+            const uint16_t* vs_base = lds_v[st] + (4 * half + tr_row) * VSTR + tr_col;
+#pragma unroll
+            for (int sl = 0; sl < SL; ++sl) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
+                    i32x2 lo = lds_read_tr16(p0);
+                    i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
+                    i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+                    for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
+                }
+            }
+        }
+
+        if (more) {
+            Copy::template to_lds<KSTR>(lds_k[st ^ 1], tid, kpre);
+            Copy::template to_lds<VSTR>(lds_v[st ^ 1], tid, vpre);
+        }
+        __syncthreads();
+    }
+
+    // ---- epilogue: O / l, L = m + log l
+#pragma unroll
+    for (int rq = 0; rq < RQ; ++rq) {
+        int qi = wave_q0 + rq * 32 + col;
+        float l = sum_both_halves(l_run[rq]);
+        float inv = 1.0f / l;
+        if (qi < N) {
+            uint16_t* orow = o + head_off + (size_t)qi * D;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    i32x2 w;
+                    w[0] = E::pack2(oacc[rq][dt][4 * g] * inv, oacc[rq][dt][4 * g + 1] * inv);
+                    w[1] = E::pack2(oacc[rq][dt][4 * g + 2] * inv, oacc[rq][dt][4 * g + 3] * inv);
+                    *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
+                }
+            if (half == 0) lse[(size_t)bh * N + qi] = (m_run[rq] * sc + log2f(l)) * kLn2;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// fp32 path (d = 64): plain fp32 FMA arithmetic with the same structure -- a query tile per
+// workgroup, K/V blocks staged in LDS, online softmax with exp2 and the scale folded in.
+// One thread owns one query row, so no cross-lane reductions are needed.
+template <int D, int BC, bool CAUSAL>
+__global__ void __launch_bounds__(64) fa_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
+                                                        const float* __restrict__ v, float* __restrict__ o,
+                                                        float* __restrict__ lse, int N, int n_qtiles, float scale) {
+    constexpr int BR = 64;
+    __shared__ float lds_k[BC * D];
+    __shared__ float lds_v[BC * D];
+    const int tid = threadIdx.x;
+    const int bh = blockIdx.x / n_qtiles, qt = blockIdx.x % n_qtiles;
+    const size_t head_off = (size_t)bh * N * D;
+    const int qi = qt * BR + tid;
+    const float sc = scale * kLog2e;
+
+    float qr[D], acc[D];
+#pragma unroll
+    for (int c = 0; c < D; ++c) {
+        qr[c] = qi < N ? q[head_off + (size_t)qi * D + c] : 0.f;
+        acc[c] = 0.f;
+    }
+    float m_run = -INFINITY, l_run = 0.f;
+    int last_q = min(qt * BR + BR, N) - 1;
+    int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+    for (int t = 0; t < n_blocks; ++t) {
+        int key0 = t * BC;
+        __syncthreads();
+        for (int e = tid; e < BC * D; e += 64) {
+            int key = key0 + e / D;
+            lds_k[e] = key < N ? k[head_off + (size_t)key0 * D + e] : 0.f;
+            lds_v[e] = key < N ? v[head_off + (size_t)key0 * D + e] : 0.f;
+        }
+        __syncthreads();
+        float s[BC];
+        float mx = -INFINITY;
+        int limit = CAUSAL ? min(qi, N - 1) : N - 1;
+#pragma unroll
+        for (int j = 0; j < BC; ++j) {
+            float a = 0.f;
+#pragma unroll
+            for (int c = 0; c < D; ++c) a = __builtin_fmaf(qr[c], lds_k[j * D + c], a);
+            s[j] = (key0 + j > limit) ? -INFINITY : a;
+            mx = fmaxf(mx, s[j]);
+        }
+        float m_new = fmaxf(m_run, mx);
+        if (m_new == -INFINITY) continue;  // row past N in a causal tail: nothing visible yet
+        float corr = fast_exp2((m_run - m_new) * sc);
+        m_run = m_new;
+        float mb = m_new * sc;
+        l_run *= corr;
+#pragma unroll
+        for (int c = 0; c < D; ++c) acc[c] *= corr;
+#pragma unroll
+        for (int j = 0; j < BC; ++j) {
+            float p = fast_exp2(__builtin_fmaf(s[j], sc, -mb));
+            l_run += p;
+#pragma unroll
+            for (int c = 0; c < D; ++c) acc[c] = __builtin_fmaf(p, lds_v[j * D + c], acc[c]);
+        }
+    }
+    if (qi < N) {
+        float inv = 1.0f / l_run;
+#pragma unroll
+        for (int c = 0; c < D; ++c) o[head_off + (size_t)qi * D + c] = acc[c] * inv;
+        lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l_run)) * kLn2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+template <typename Tag, int D, int BC, int NW, int RQ>
+static int launch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+                        float scale, int causal, hipStream_t stream) {
+    constexpr int BR = NW * 32 * RQ;
+    int n_qtiles = (N + BR - 1) / BR;
+    long total = (long)B * H * n_qtiles;
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(NW * 64);
+    auto qp = static_cast<const uint16_t*>(q);
+    auto kp = static_cast<const uint16_t*>(k);
+    auto vp = static_cast<const uint16_t*>(v);
+    auto op = static_cast<uint16_t*>(o);
+    if (causal)
+        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, true>), grid, block, 0, stream, qp, kp, vp, op,
+                           lse, N, n_qtiles, (int)total, scale);
+    else
+        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, false>), grid, block, 0, stream, qp, kp, vp, op,
+                           lse, N, n_qtiles, (int)total, scale);
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
+template <typename Tag>
+static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+                          int d, float scale, int causal, hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_16bit<Tag, 64, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 128: return launch_16bit<Tag, 128, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 256: return launch_16bit<Tag, 256, 32, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        default: return FA_ERR_UNSUPPORTED;
+    }
+}
+
+int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                    float scale, int causal, hipStream_t stream) {
+    return dispatch_16bit<bf16_tag>(q, k, v, o, lse, B, H, N, d, scale, causal, stream);
+}
+
+int launch_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                   float scale, int causal, hipStream_t stream) {
+    return dispatch_16bit<f16_tag>(q, k, v, o, lse, B, H, N, d, scale, causal, stream);
+}
+
+int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                   float scale, int causal, hipStream_t stream) {
+    if (d != 64) return FA_ERR_UNSUPPORTED;
+    constexpr int BR = 64;
+    int n_qtiles = (N + BR - 1) / BR;
+    long total = (long)B * H * n_qtiles;
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(64);
+    auto qp = static_cast<const float*>(q);
+    auto kp = static_cast<const float*>(k);
+    auto vp = static_cast<const float*>(v);
+    auto op = static_cast<float*>(o);
+    if (causal)
+        hipLaunchKernelGGL((fa_fwd_f32_kernel<64, 32, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N, n_qtiles,
+                           scale);
+    else
+        hipLaunchKernelGGL((fa_fwd_f32_kernel<64, 32, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
+                           n_qtiles, scale);
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
+}  // namespace fa

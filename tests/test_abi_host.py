@@ -1,0 +1,81 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2407_08608_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "fa_mi355.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fa_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_status_strings():
+    assert binding.status_string(0) == "ok"
+    seen = {binding.status_string(s) for s in range(8)}
+    assert len(seen) == 8
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_fa_fwd_rejects_bad_arguments_without_launching():
+    L = binding.lib()
+    p = ctypes.c_void_p(0x1000)  # never dereferenced: validation fails first
+    ok = dict(B=1, H=1, N=16, d=64, scale=0.125, causal=0, dtype=binding.FA_BF16)
+
+    def call(q=p, k=p, v=p, o=p, lse=p, **kw):
+        a = dict(ok, **kw)
+        return L.fa_fwd(q, k, v, o, lse, a["B"], a["H"], a["N"], a["d"], a["scale"], a["causal"], a["dtype"], None)
+
+    assert call(q=None) == 1 and call(lse=None) == 1
+    assert call(N=0) == 2 and call(B=-1) == 2 and call(scale=0.0) == 2 and call(scale=float("nan")) == 2
+    assert call(causal=2) == 2
+    assert call(dtype=7) == 3
+    assert call(d=96) == 4
+    assert call(dtype=binding.FA_F32, d=128, q=ctypes.c_void_p(0x1008)) == 5
+    assert call(k=ctypes.c_void_p(0x1004)) == 5
+
+
+def test_fp8_and_bwd_entry_points_validate():
+    L = binding.lib()
+    p = ctypes.c_void_p(0x1000)
+    assert L.fa_fwd_fp8(p, p, p, p, p, p, p, p, 1, 1, 16, 128, 64, 0.1, 0, None) == 4  # block_rows != 128
+    assert L.fa_fwd_fp8(p, p, p, None, p, p, p, p, 1, 1, 16, 128, 128, 0.1, 0, None) == 1
+    assert L.fa_fp8_quant_hadamard(p, binding.FA_FP8_E4M3, p, p, 1, 1, 16, 128, 128, None, 0, None) == 4
+    assert L.fa_fp8_quant_hadamard(p, 9, p, p, 1, 1, 16, 128, 128, None, 0, None) == 3
+    assert L.fa_fp8_quant_hadamard(p, binding.FA_BF16, p, p, 1, 1, 0, 128, 128, None, 0, None) == 2
+    assert L.fa_bwd_workspace_bytes(1, 1, 16, 64, binding.FA_BF16) == 0  # unsupported head dim
+    args = [p] * 10 + [0, 1, 1, 16, 64, 0.1, 0, binding.FA_BF16, None]
+    assert L.fa_bwd(*args) == 4
+    args = [p] * 9 + [None, 0, 1, 1, 16, 128, 0.1, 0, binding.FA_BF16, None]
+    assert L.fa_bwd(*args) == 6
+
+
+def test_flop_accounting_matches_the_papers_ablation_table():
+    import json
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_values.json")))
+    row = g["ablation_full_method"]
+    fl = binding.attention_flops(row["batch"], row["nheads"], row["seqlen"], row["hdim"], row["causal"])
+    assert fl / (row["time_ms"] * 1e-3) / 1e12 == pytest.approx(row["tflops"], abs=0.6)
+    for name in ("ablation_no_pipelining", "ablation_no_warp_specialization"):
+        assert fl / (g[name]["time_ms"] * 1e-3) / 1e12 == pytest.approx(g[name]["tflops"], abs=0.6)
+    assert binding.attention_flops(1, 1, 8, 4, True) == 0.5 * binding.attention_flops(1, 1, 8, 4, False)
+    assert binding.attention_flops(1, 1, 8, 4, False, backward=True) == g["flops_rule"]["bwd_over_fwd"] * binding.attention_flops(1, 1, 8, 4, False)
+    # matmul FLOPs per exponential at head dim 128: 4*N^2*d / N^2 = 512
+    e = g["exp_vs_matmul"]
+    assert binding.attention_flops(1, 1, 64, e["hdim"], False) / (64 * 64) == e["matmul_flops_per_exp"]
