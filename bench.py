@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused attention forward on one MI355X.
+
+One step = one pass of the paper's forward sweep at head dimension 128 (section 4.1,
+"Benchmark settings": 16k tokens in total, hidden size 2048 = 16 heads, sequence length
+512 ... 16k with batch = 16384 / seqlen), non-causal and causal: 12 launches of `fa_fwd` on
+bf16 inputs resident in HBM.  FLOPs follow the paper's accounting (4 * N^2 * d * heads *
+batch, halved when causal).  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+SEQLENS = (512, 1024, 2048, 4096, 8192, 16384)
+HEAD_DIM = 128
+PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
+PEAK_FP8_TFLOPS = 5000.0
+
+
+def _cpu_baseline():
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample."""
+    import numpy as np
+    import oracle
+    from paper_2407_08608_amd import binding, inputs
+    N, d, heads = 4096, HEAD_DIM, 4
+    q, k, v = inputs.qkv(123, 1, heads, N, d, "bf16")
+    q, k, v = (t.double().numpy() for t in (q, k, v))
+    t0 = time.perf_counter()
+    oracle.attention_fwd(q, k, v, d ** -0.5, False)
+    dt = time.perf_counter() - t0
+    flops = binding.attention_flops(1, heads, N, d, False)
+    return {"value": flops / dt / 1e12, "unit": "TFLOPs/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{heads} of the 64 (batch, head) slices of the seqlen-{N} non-causal point, all rows, fp64",
+            "seconds": round(dt, 2)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extra", action="store_true", help="skip the untimed per-config table")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
+                 "(the path shards over batch and heads without communication)")
+
+    import torch
+    from paper_2407_08608_amd import binding, inputs
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d = HEAD_DIM
+    scale = d ** -0.5
+
+    # inputs resident in HBM before anything is timed
+    work = []
+    for N in SEQLENS:
+        B, H = inputs.benchmark_shape(N, d)
+        q, k, v = (t.to(dev) for t in inputs.qkv(1000 + N, B, H, N, d, "bf16"))
+        o = torch.empty_like(q)
+        lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+        work.append((N, B, H, q, k, v, o, lse))
+    stream = torch.cuda.current_stream()
+
+    def one_step(events=None):
+        for causal in (False, True):
+            for (N, B, H, q, k, v, o, lse) in work:
+                if events is not None:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(stream)
+                binding.fa_fwd(q, k, v, scale, causal, o=o, lse=lse)
+                if events is not None:
+                    e1.record(stream)
+                    events.append((N, causal, e0, e1))
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    step_flops = sum(binding.attention_flops(B, H, N, d, c) for c in (False, True) for (N, B, H, *_r) in work)
+    ms_per_step = elapsed / args.steps * 1e3
+    value = step_flops / (elapsed / args.steps) / 1e12
+
+    # dominant kernel: the non-causal d=128 bf16 forward (about two thirds of the step's time)
+    dur_ms, flops_nc, per_point = 0.0, 0.0, {}
+    for (N, causal, e0, e1) in events:
+        ms = e0.elapsed_time(e1)
+        per_point.setdefault((N, causal), []).append(ms)
+        if not causal:
+            dur_ms += ms
+            B, H = inputs.benchmark_shape(N, d)
+            flops_nc += binding.attention_flops(B, H, N, d, False)
+    n_launch = args.steps * len(SEQLENS)
+    achieved = flops_nc / (dur_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                "kernel": "fa_fwd_16bit_kernel<bf16, d=128, causal=false>",
+                "avg_launch_ms": round(dur_ms / n_launch, 4), "launches": n_launch}
+
+    points = {}
+    for (N, causal), ms_list in sorted(per_point.items()):
+        ms = sum(ms_list) / len(ms_list)
+        B, H = inputs.benchmark_shape(N, d)
+        points[f"N{N}_{'causal' if causal else 'full'}"] = {
+            "ms": round(ms, 4), "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1)}
+
+    out = {
+        "metric": "fwd attention TFLOPs/s bf16, hdim 128, seqlen 512-16k (causal + non-causal sweep aggregate)",
+        "value": round(value, 2), "unit": "TFLOPs/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "attention fwd bf16, head_dim 128, 16 heads, seqlen {512..16k} x batch 16384/seqlen, "
+                               "non-causal + causal (12 launches per step)"},
+        "roofline": roofline,
+        "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
+        "points": points,
+    }
+    if not args.no_extra:
+        out["extra"] = extra_table(torch, binding, inputs, dev)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = _cpu_baseline()
+    print(json.dumps(out))
+
+
+def _time_call(torch, fn, reps=10, warm=2):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def extra_table(torch, binding, inputs, dev):
+    """Untimed-by-the-headline table: other head dimensions (TFLOPs/s at seqlen 512 / 4k / 16k)."""
+    table = {}
+    for d in (64, 256):
+        for N in (512, 4096, 16384):
+            B, H = inputs.benchmark_shape(N, d)
+            q, k, v = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(3))
+            o = torch.empty_like(q)
+            lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+            for causal in (False, True):
+                ms = _time_call(torch, lambda: binding.fa_fwd(q, k, v, d ** -0.5, causal, o=o, lse=lse))
+                table[f"fwd_bf16_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
+                    "ms": round(ms, 4), "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1)}
+    return table
+
+
+if __name__ == "__main__":
+    main()

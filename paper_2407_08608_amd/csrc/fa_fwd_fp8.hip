@@ -1,0 +1,296 @@
+// FP8 (e4m3) forward attention for gfx950 (paper section 3.3).
+//
+// Same tiling as the 16-bit kernel (Algorithm 1), on v_mfma_f32_32x32x64_f8f6f4: both GEMMs
+// contract 64 elements per instruction and a lane holds 32 bytes of an operand.
+//   * Block quantisation: a block of S is rescaled by s_Q[i] * s_K[j], folded into the exp2
+//     multiplier, so it costs nothing per element.  The output accumulator is kept in units
+//     of the current V block's scale and converted when the block changes.
+//   * Layout conformance: V is stored d-contiguous but must be contracted over keys.  The
+//     transposing LDS read (ds_read_b64_tr_b8) hands a lane 8 consecutive keys of one column,
+//     while the fp32 accumulator of S^T gives a lane-half alternating groups of 4 rows.  The
+//     rows of the K operand are therefore permuted (row i of the MFMA reads key pi(i)) so
+//     that each lane-half ends up owning two runs of 8 consecutive keys; P~ then goes from
+//     accumulator registers to operand registers with conversions only, no cross-lane moves.
+//     This is the same idea as the paper's register permutation plus matching V-row
+//     permutation, rederived for the gfx950 layouts.
+//   * P~ = exp2(s - m + 8): the bias uses more of e4m3's range (P~ <= 256 < 448) and cancels
+//     in O / l; L subtracts it again.
+#include "fa_device.h"
+#include "fa_launch.h"
+
+namespace fa {
+
+constexpr float kPBias = 8.0f;
+
+static __device__ __forceinline__ f32x16 mma_fp8(i32x8 a, i32x8 b, f32x16 c) {
+    // cbsz = blgp = 0: both operands e4m3; scale exponents 127 = 1.0
+    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+}
+
+// key held in MFMA row i of a 32-key tile
+static __device__ __forceinline__ int key_of_row(int i) {
+    int g = i >> 3, hb = (i >> 2) & 1, r = i & 3;
+    return 16 * (g >> 1) + 8 * hb + 4 * (g & 1) + r;
+}
+
+template <int D, int BC, int NW, bool CAUSAL, bool SCALED>
+__global__ void __launch_bounds__(NW * 64, D <= 128 ? 2 : 1)
+fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
+                  const float* __restrict__ q_scale, const float* __restrict__ k_scale,
+                  const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
+                  int n_qtiles, int total_wg, int n_sblocks, float scale) {
+    constexpr int NT = NW * 64;
+    constexpr int BR = NW * 32;
+    constexpr int KSTR = D + 16;  // bytes per LDS row
+    constexpr int VSTR = D + 32;
+    constexpr int KT = BC / 32;
+    constexpr int KS = D / 64;    // MFMA steps along the head dimension
+    constexpr int DT = D / 32;
+    constexpr int SL = BC / 64;   // MFMA steps along the keys
+    constexpr int CPR = D / 16;   // 16-byte chunks per row
+    constexpr int CPT = BC * CPR / NT;
+    static_assert(BC % 64 == 0 && 128 % BC == 0, "key block must tile the 128-row quantisation block");
+    static_assert((BC * CPR) % NT == 0, "tile must divide evenly over the workgroup");
+
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][BC * KSTR];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][BC * VSTR];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int bh = id / n_qtiles;
+    int qt = id % n_qtiles;
+    if (CAUSAL) qt = n_qtiles - 1 - qt;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint8_t* qh = q + head_off;
+    const uint8_t* kh = k + head_off;
+    const uint8_t* vh = v + head_off;
+    const int wave_q0 = qt * BR + wave * 32;
+
+    float sq = 1.0f;
+    if constexpr (SCALED) sq = q_scale[(size_t)bh * n_sblocks + min(wave_q0 / 128, n_sblocks - 1)];
+    const float sc_q = scale * kLog2e * sq;
+
+    i32x8 qreg[KS];
+    {
+        int row = wave_q0 + col;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            i32x4 z = {0, 0, 0, 0};
+            const uint8_t* p = qh + (size_t)row * D + ks * 64 + half * 32;
+            i32x4 lo = row < N ? *reinterpret_cast<const i32x4*>(p) : z;
+            i32x4 hi = row < N ? *reinterpret_cast<const i32x4*>(p + 16) : z;
+            qreg[ks] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+    }
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;  // m in log2 units of the real (scaled) scores
+    float sv_cur = 1.0f;
+
+    int last_q = min(qt * BR + BR, N) - 1;
+    int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+
+    auto load_tile = [&](const uint8_t* head, int key0, i32x4 (&regs)[CPT]) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int c = tid + i * NT;
+            int row = c / CPR, cc = c % CPR;
+            int key = key0 + row;
+            i32x4 z = {0, 0, 0, 0};
+            regs[i] = key < N ? *reinterpret_cast<const i32x4*>(head + (size_t)key * D + cc * 16) : z;
+        }
+    };
+    auto store_tile = [&](uint8_t* lds, int stride, const i32x4 (&regs)[CPT]) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int c = tid + i * NT;
+            int row = c / CPR, cc = c % CPR;
+            *reinterpret_cast<i32x4*>(lds + row * stride + cc * 16) = regs[i];
+        }
+    };
+
+    i32x4 kpre[CPT], vpre[CPT];
+    load_tile(kh, 0, kpre);
+    load_tile(vh, 0, vpre);
+    store_tile(lds_k[0], KSTR, kpre);
+    store_tile(lds_v[0], VSTR, vpre);
+    __syncthreads();
+
+    const int krow = key_of_row(col);  // key (within a 32-key tile) this lane's A row reads
+    const int tr_row = (lane & 15) >> 1;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 8 * (lane & 1);
+
+    for (int t = 0; t < n_blocks; ++t) {
+        const int st = t & 1;
+        const int key0 = t * BC;
+        const bool more = (t + 1 < n_blocks);
+        if (more) {
+            load_tile(kh, key0 + BC, kpre);
+            load_tile(vh, key0 + BC, vpre);
+        }
+        const bool wave_active = !CAUSAL || key0 <= wave_q0 + 31;
+        if (wave_active) {
+            float sk = 1.0f, sv_new = 1.0f;
+            if constexpr (SCALED) {
+                sk = k_scale[(size_t)bh * n_sblocks + key0 / 128];
+                sv_new = v_scale[(size_t)bh * n_sblocks + key0 / 128];
+            }
+            const float sc = sc_q * sk;
+
+            // ---- GEMM0: S^T = K_j Q_i^T (rows permuted by key_of_row)
+            f32x16 sacc[KT];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    const uint8_t* p = lds_k[st] + (kt * 32 + krow) * KSTR + ks * 64 + half * 32;
+                    i32x4 lo = *reinterpret_cast<const i32x4*>(p);
+                    i32x4 hi = *reinterpret_cast<const i32x4*>(p + 16);
+                    i32x8 a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    sacc[kt] = mma_fp8(a, qreg[ks], sacc[kt]);
+                }
+
+            const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
+            if (need_mask) {
+                int qi = wave_q0 + col;
+                int limit = CAUSAL ? min(qi, N - 1) : N - 1;
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        // register r of lane-half `half` is MFMA row 8*(r/4) + 4*half + r%4
+                        int key = key0 + kt * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+                        if (key > limit) sacc[kt][r] = -INFINITY;
+                    }
+            }
+
+            // ---- online softmax in log2 units of the real scores
+            float mx = sacc[0][0];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
+            mx = max_both_halves(mx) * sc;
+            float m_new = fmaxf(m_run, mx);
+            float corr = fast_exp2(m_run - m_new);
+            m_run = m_new;
+            const float mb = m_new - kPBias;
+            float psum = 0.f;
+            i32x8 pb[SL];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                float p[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    p[r] = fast_exp2(__builtin_fmaf(sacc[kt][r], sc, -mb));
+                    psum += p[r];
+                }
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    int word = 0;
+                    word = __builtin_amdgcn_cvt_pk_fp8_f32(p[4 * w], p[4 * w + 1], word, false);
+                    word = __builtin_amdgcn_cvt_pk_fp8_f32(p[4 * w + 2], p[4 * w + 3], word, true);
+                    pb[kt >> 1][4 * (kt & 1) + w] = word;
+                }
+            }
+            l_run = l_run * corr + psum;
+            // accumulator changes units when the V block (and its scale) changes
+            float f = corr * (sv_cur / sv_new);
+            sv_cur = sv_new;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
+
+            // ---- GEMM1: O^T += V_j^T P^T
+            const uint8_t* vs_base = lds_v[st] + (8 * half + tr_row) * VSTR + tr_col;
+#pragma unroll
+            for (int sl = 0; sl < SL; ++sl)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    i32x8 a;
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        i32x2 w = lds_read_tr8(vs_base + (sl * 64 + 16 * u) * VSTR + dt * 32);
+                        a[2 * u] = w[0];
+                        a[2 * u + 1] = w[1];
+                    }
+                    oacc[dt] = mma_fp8(a, pb[sl], oacc[dt]);
+                }
+        }
+        if (more) {
+            store_tile(lds_k[st ^ 1], KSTR, kpre);
+            store_tile(lds_v[st ^ 1], VSTR, vpre);
+        }
+        __syncthreads();
+    }
+
+    int qi = wave_q0 + col;
+    float l = sum_both_halves(l_run);
+    float inv = sv_cur / l;
+    if (qi < N) {
+        uint16_t* orow = o + head_off + (size_t)qi * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                i32x2 w;
+                w[0] = Elem<bf16_tag>::pack2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
+                w[1] = Elem<bf16_tag>::pack2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
+                *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
+            }
+        if (half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
+    }
+}
+
+template <int D, int BC, int NW>
+static int launch_fp8(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
+                      const float* vs, void* o, float* lse, int B, int H, int N, float scale, int causal,
+                      hipStream_t stream) {
+    constexpr int BR = NW * 32;
+    int n_qtiles = (N + BR - 1) / BR;
+    int n_sblocks = (N + 127) / 128;
+    long total = (long)B * H * n_qtiles;
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(NW * 64);
+    auto qp = static_cast<const uint8_t*>(q8);
+    auto kp = static_cast<const uint8_t*>(k8);
+    auto vp = static_cast<const uint8_t*>(v8);
+    auto op = static_cast<uint16_t*>(o);
+    const bool scaled = qs != nullptr;
+#define FA_LAUNCH_FP8(C, S)                                                                                       \
+    hipLaunchKernelGGL((fa_fwd_fp8_kernel<D, BC, NW, C, S>), grid, block, 0, stream, qp, kp, vp, qs, ks, vs, op, \
+                       lse, N, n_qtiles, (int)total, n_sblocks, scale)
+    if (causal) {
+        if (scaled) FA_LAUNCH_FP8(true, true); else FA_LAUNCH_FP8(true, false);
+    } else {
+        if (scaled) FA_LAUNCH_FP8(false, true); else FA_LAUNCH_FP8(false, false);
+    }
+#undef FA_LAUNCH_FP8
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
+int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
+                   const float* v_scale, void* o, float* lse, int B, int H, int N, int d, float scale, int causal,
+                   hipStream_t stream) {
+    switch (d) {
+        case 64: return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+        case 128: return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+        case 256: return launch_fp8<256, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+        default: return FA_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace fa
