@@ -25,19 +25,19 @@ PEAK_FP8_TFLOPS = 5000.0
 
 def _cpu_baseline():
     """The fp64 oracle, as it stands, timed on the host cores on a bounded sample."""
-    import numpy as np
     import oracle
     from paper_2407_08608_amd import binding, inputs
-    N, d, heads = 4096, HEAD_DIM, 4
-    q, k, v = inputs.qkv(123, 1, heads, N, d, "bf16")
+    N, d = 8192, HEAD_DIM
+    B, H = inputs.benchmark_shape(N, d)
+    q, k, v = inputs.qkv(123, B, H, N, d, "bf16")
     q, k, v = (t.double().numpy() for t in (q, k, v))
     t0 = time.perf_counter()
     oracle.attention_fwd(q, k, v, d ** -0.5, False)
     dt = time.perf_counter() - t0
-    flops = binding.attention_flops(1, heads, N, d, False)
-    return {"value": flops / dt / 1e12, "unit": "TFLOPs/s", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"{heads} of the 64 (batch, head) slices of the seqlen-{N} non-causal point, all rows, fp64",
-            "seconds": round(dt, 2)}
+    flops = binding.attention_flops(B, H, N, d, False)
+    return {"value": round(flops / dt / 1e12, 4), "unit": "TFLOPs/s", "cores": oracle.num_threads(),
+            "kind": "oracle", "seconds": round(dt, 2),
+            "sample": f"the whole seqlen-{N} non-causal point of the sweep (batch {B}, {H} heads), fp64"}
 
 
 def main():
@@ -153,9 +153,13 @@ def _time_call(torch, fn, reps=10, warm=2):
 
 
 def extra_table(torch, binding, inputs, dev):
-    """Untimed-by-the-headline table: other head dimensions (TFLOPs/s at seqlen 512 / 4k / 16k)."""
+    """Outside the timed headline: the other rows of the path at three sequence lengths each."""
     table = {}
-    for d in (64, 256):
+
+    def tf(B, H, N, d, causal, ms, backward=False):
+        return round(binding.attention_flops(B, H, N, d, causal, backward) / ms / 1e9, 1)
+
+    for d in (64, 256):  # bf16 forward at the other head dimensions
         for N in (512, 4096, 16384):
             B, H = inputs.benchmark_shape(N, d)
             q, k, v = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(3))
@@ -164,7 +168,37 @@ def extra_table(torch, binding, inputs, dev):
             for causal in (False, True):
                 ms = _time_call(torch, lambda: binding.fa_fwd(q, k, v, d ** -0.5, causal, o=o, lse=lse))
                 table[f"fwd_bf16_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
-                    "ms": round(ms, 4), "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1)}
+                    "ms": round(ms, 4), "tflops": tf(B, H, N, d, causal, ms)}
+    for d in (128, 256):  # FP8: pre-pass (HBM-bound) and forward on heavy-tailed inputs
+        for N in (512, 4096, 16384):
+            B, H = inputs.benchmark_shape(N, d)
+            q, k, v = (t.to(dev) for t in inputs.qkv(7, B, H, N, d, "bf16", heavy_tailed=True))
+            signs = inputs.random_signs(7, d).to(dev)
+            q8, qs = binding.fa_fp8_quant_hadamard(q, signs)
+            k8, ks = binding.fa_fp8_quant_hadamard(k, signs)
+            v8, vs = binding.fa_fp8_quant_hadamard(v, None)
+            ms = _time_call(torch, lambda: binding.fa_fp8_quant_hadamard(q, signs, x8=q8, scales=qs))
+            table[f"quant_hadamard_d{d}_N{N}"] = {"ms": round(ms, 4), "GBps": round(q.numel() * 3 / ms / 1e6, 1)}
+            o = torch.empty_like(q)
+            lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+            for causal in (False, True):
+                ms = _time_call(torch, lambda: binding.fa_fwd_fp8(q8, k8, v8, qs, ks, vs, d ** -0.5, causal,
+                                                                  o=o, lse=lse))
+                table[f"fwd_fp8_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
+                    "ms": round(ms, 4), "tflops": tf(B, H, N, d, causal, ms),
+                    "frac_of_fp8_peak": round(tf(B, H, N, d, causal, ms) / PEAK_FP8_TFLOPS, 4)}
+    d = 128  # bf16 backward
+    for N in (1024, 4096, 16384):
+        B, H = inputs.benchmark_shape(N, d)
+        q, k, v, do = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(4))
+        ws = torch.empty(binding.fa_bwd_workspace_bytes(B, H, N, d), device=dev, dtype=torch.uint8)
+        dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+        for causal in (False, True):
+            o, lse = binding.fa_fwd(q, k, v, d ** -0.5, causal)
+            ms = _time_call(torch, lambda: binding.fa_bwd(q, k, v, o, lse, do, d ** -0.5, causal, dq=dq, dk=dk,
+                                                          dv=dv, workspace=ws), reps=5)
+            table[f"bwd_bf16_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
+                "ms": round(ms, 4), "tflops": tf(B, H, N, d, causal, ms, backward=True)}
     return table
 
 
