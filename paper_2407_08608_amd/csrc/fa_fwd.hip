@@ -12,6 +12,8 @@
 
 namespace fa {
 
+constexpr float kLazyLog2 = 8.0f;
+
 template <int D, int BC, int NT>
 struct TileCopy {
     static constexpr int kChunksPerRow = D / 8;  // 16-byte chunks of 8 16-bit elements
@@ -131,12 +133,7 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         if (wave_active) {
             // ---- GEMM0: S^T = K_j Q_i^T
             f32x16 sacc[RQ][KT];
-#pragma unroll
-            for (int rq = 0; rq < RQ; ++rq)
-#pragma unroll
-                for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) sacc[rq][kt][r] = 0.f;
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
@@ -144,7 +141,8 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 for (int kt = 0; kt < KT; ++kt) {
                     i32x4 a = *reinterpret_cast<const i32x4*>(ks_base + kt * 32 * KSTR + ks * 16);
 #pragma unroll
-                    for (int rq = 0; rq < RQ; ++rq) sacc[rq][kt] = E::mma(a, qreg[rq][ks], sacc[rq][kt]);
+                    for (int rq = 0; rq < RQ; ++rq)
+                        sacc[rq][kt] = E::mma(a, qreg[rq][ks], ks == 0 ? zero : sacc[rq][kt]);
                 }
             }
 
@@ -175,10 +173,20 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 #pragma unroll
                     for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[rq][kt][r]);
                 mx = max_both_halves(mx);
-                float m_new = fmaxf(m_run[rq], mx);
-                float corr = fast_exp2((m_run[rq] - m_new) * sc);
-                m_run[rq] = m_new;
-                float mb = m_new * sc;
+                // The reference maximum is raised only when the block's maximum exceeds it by more
+                // than 2^kLazyLog2 in the exponent: P~ <= 2^kLazyLog2 otherwise, the factor cancels
+                // in O / l, and the O rescale (the costliest VALU step) is skipped on most blocks.
+                const bool raise = (mx - m_run[rq]) * sc > kLazyLog2;
+                if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                    float corr = raise ? fast_exp2((m_run[rq] - mx) * sc) : 1.0f;
+                    m_run[rq] = raise ? mx : m_run[rq];
+                    l_run[rq] *= corr;
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) oacc[rq][dt][r] *= corr;
+                }
+                float mb = m_run[rq] * sc;
                 float psum = 0.f;
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt) {
@@ -196,11 +204,7 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                         pb[rq][2 * kt + s2] = w;
                     }
                 }
-                l_run[rq] = l_run[rq] * corr + psum;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) oacc[rq][dt][r] *= corr;
+                l_run[rq] += psum;
             }
 
             // ---- GEMM1: O^T += V_j^T P^T
