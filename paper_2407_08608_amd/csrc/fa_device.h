@@ -108,6 +108,14 @@ static __device__ __forceinline__ float sum_both_halves(float x) {
     return p.lo + p.hi;
 }
 
+// Raw buffer access to a caller tensor: reads past `bytes` return zero instead of faulting.
+static __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_buffer(const void* base, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, (int)bytes, 0x00020000);
+}
+static __device__ __forceinline__ i32x4 buffer_load_16B(__amdgpu_buffer_rsrc_t rsrc, int byte_off) {
+    return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0));
+}
+
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // The chip deals consecutive workgroup ids round-robin to its 8 XCDs, each with a private

@@ -7,6 +7,7 @@
 // exp(m_old - m_new); epilogue O / l and L = m + log l.  K_j and V_j are staged through a
 // double-buffered LDS ring that the next block's global loads fill while the current block
 // is being computed (the role the producer warpgroup plays in the paper).
+#include <stdlib.h>
 #include "fa_device.h"
 #include "fa_launch.h"
 
@@ -21,17 +22,14 @@ struct TileCopy {
     static constexpr int kPerThread = kChunks / NT;
     static_assert(kChunks % NT == 0, "tile must divide evenly over the workgroup");
 
-    // rows past N read as zero so that masked probabilities multiply finite values
-    static __device__ __forceinline__ void from_global(const uint16_t* head, int key0, int N, int tid,
+    // A [BC][D] tile of a row-major [N][D] head is one contiguous run of bytes, so chunk c of the
+    // tile sits at tile_byte_off + 16*c: no per-row address arithmetic.  Rows past N fall outside
+    // the buffer resource and read as zero (their scores are masked anyway).
+    static __device__ __forceinline__ void from_global(__amdgpu_buffer_rsrc_t head, int tile_byte_off, int tid,
                                                        i32x4 (&regs)[kPerThread]) {
 #pragma unroll
-        for (int i = 0; i < kPerThread; ++i) {
-            int c = tid + i * NT;
-            int row = c / kChunksPerRow, col = c % kChunksPerRow;
-            int key = key0 + row;
-            i32x4 z = {0, 0, 0, 0};
-            regs[i] = key < N ? *reinterpret_cast<const i32x4*>(head + (size_t)key * D + col * 8) : z;
-        }
+        for (int i = 0; i < kPerThread; ++i)
+            regs[i] = buffer_load_16B(head, tile_byte_off + (tid + i * NT) * 16);
     }
     template <int STRIDE>
     static __device__ __forceinline__ void to_lds(uint16_t* lds, int tid, const i32x4 (&regs)[kPerThread]) {
@@ -84,12 +82,10 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     i32x4 qreg[RQ][KS];
 #pragma unroll
     for (int rq = 0; rq < RQ; ++rq) {
-        int row = wave_q0 + rq * 32 + col;
+        int row = min(wave_q0 + rq * 32 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            i32x4 z = {0, 0, 0, 0};
-            qreg[rq][ks] = row < N ? *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8) : z;
-        }
+        for (int ks = 0; ks < KS; ++ks)
+            qreg[rq][ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
     }
 
     f32x16 oacc[RQ][DT];
@@ -109,8 +105,10 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
 
     i32x4 kpre[Copy::kPerThread], vpre[Copy::kPerThread];
-    Copy::from_global(kh, 0, N, tid, kpre);
-    Copy::from_global(vh, 0, N, tid, vpre);
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_buffer(kh, (uint32_t)N * D * 2);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_buffer(vh, (uint32_t)N * D * 2);
+    Copy::from_global(k_rsrc, 0, tid, kpre);
+    Copy::from_global(v_rsrc, 0, tid, vpre);
     Copy::template to_lds<KSTR>(lds_k[0], tid, kpre);
     Copy::template to_lds<VSTR>(lds_v[0], tid, vpre);
     __syncthreads();
@@ -123,10 +121,12 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         const int st = t & 1;
         const int key0 = t * BC;
         const bool more = (t + 1 < n_blocks);
+#ifndef FA_EXP_NOSTAGE
         if (more) {
-            Copy::from_global(kh, key0 + BC, N, tid, kpre);
-            Copy::from_global(vh, key0 + BC, N, tid, vpre);
+            Copy::from_global(k_rsrc, (key0 + BC) * D * 2, tid, kpre);
+            Copy::from_global(v_rsrc, (key0 + BC) * D * 2, tid, vpre);
         }
+#endif
 
         // a wave whose queries all precede this block has nothing to add (causal)
         const bool wave_active = !CAUSAL || key0 <= wave_q0 + 32 * RQ - 1;
@@ -135,6 +135,9 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             f32x16 sacc[RQ][KT];
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
+#ifdef FA_SETPRIO
+            __builtin_amdgcn_s_setprio(1);
+#endif
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
@@ -146,6 +149,9 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 }
             }
 
+#ifdef FA_SETPRIO
+            __builtin_amdgcn_s_setprio(0);
+#endif
             // ---- mask: keys past N, and keys after the query when causal
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
             if (need_mask) {
@@ -193,8 +199,15 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     float p[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
+#if defined(FA_EXP_NOEXP)
+                        p[r] = __builtin_fmaf(sacc[rq][kt][r], sc, -mb);
+                        psum += p[r];
+#elif defined(FA_EXP_NOSOFTMAX)
+                        p[r] = sacc[rq][kt][r];
+#else
                         p[r] = fast_exp2(__builtin_fmaf(sacc[rq][kt][r], sc, -mb));
                         psum += p[r];
+#endif
                     }
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
@@ -213,21 +226,29 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             for (int sl = 0; sl < SL; ++sl) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
+#ifdef FA_EXP_NOTR
+                    i32x4 a = *reinterpret_cast<const i32x4*>(reinterpret_cast<const char*>(lds_v[st]) + col * 272 + half * 16 + dt * 32 + sl * (BC * VSTR * 2 / SL / 16 * 16 - 640));
+#else
                     const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
                     i32x2 lo = lds_read_tr16(p0);
                     i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
                     i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+#endif
 #pragma unroll
                     for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
                 }
             }
         }
 
+#ifndef FA_EXP_NOSTAGE
         if (more) {
             Copy::template to_lds<KSTR>(lds_k[st ^ 1], tid, kpre);
             Copy::template to_lds<VSTR>(lds_v[st ^ 1], tid, vpre);
         }
+#endif
+#ifndef FA_EXP_NOBARRIER
         __syncthreads();
+#endif
     }
 
     // ---- epilogue: O / l, L = m + log l
@@ -349,7 +370,16 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
                           int d, float scale, int causal, hipStream_t stream) {
     switch (d) {
         case 64: return launch_16bit<Tag, 64, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-        case 128: return launch_16bit<Tag, 128, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 128: {
+            const char* e = getenv("FA_FWD_VARIANT");  // EXPERIMENT
+            int var = e ? atoi(e) : 0;
+            if (var == 1) return launch_16bit<Tag, 128, 64, 4, 2>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (var == 2) return launch_16bit<Tag, 128, 64, 8, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (var == 3) return launch_16bit<Tag, 128, 32, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (var == 4) return launch_16bit<Tag, 128, 128, 8, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (var == 5) return launch_16bit<Tag, 128, 32, 4, 2>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            return launch_16bit<Tag, 128, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        }
         case 256: return launch_16bit<Tag, 256, 32, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
