@@ -7,7 +7,6 @@
 // exp(m_old - m_new); epilogue O / l and L = m + log l.  K_j and V_j are staged through a
 // double-buffered LDS ring that the next block's global loads fill while the current block
 // is being computed (the role the producer warpgroup plays in the paper).
-#include <stdlib.h>
 #include "fa_device.h"
 #include "fa_launch.h"
 
@@ -42,7 +41,7 @@ struct TileCopy {
     }
 };
 
-template <typename Tag, int D, int BC, int NW, int RQ, bool CAUSAL>
+template <typename Tag, int D, int BC, int NW, int RQ, int PD, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, (RQ == 1 && D <= 128) ? 2 : 1)
 fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
@@ -111,6 +110,13 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     Copy::from_global(v_rsrc, 0, tid, vpre);
     Copy::template to_lds<KSTR>(lds_k[0], tid, kpre);
     Copy::template to_lds<VSTR>(lds_v[0], tid, vpre);
+    // Pin the Q loads' completion here.  Left to itself the compiler sinks them to the loop
+    // entry, and the vmcnt waits it then needs at their first use sit inside the loop body,
+    // where on every later iteration they would wait for the K/V prefetch just issued.
+#pragma unroll
+    for (int rq = 0; rq < RQ; ++rq)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[rq][ks]));
     __syncthreads();
 
     // transposing V read: lane -> (row within a 4-key group, 4-column chunk) of its 16-lane group
@@ -121,12 +127,10 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         const int st = t & 1;
         const int key0 = t * BC;
         const bool more = (t + 1 < n_blocks);
-#ifndef FA_EXP_NOSTAGE
         if (more) {
             Copy::from_global(k_rsrc, (key0 + BC) * D * 2, tid, kpre);
             Copy::from_global(v_rsrc, (key0 + BC) * D * 2, tid, vpre);
         }
-#endif
 
         // a wave whose queries all precede this block has nothing to add (causal)
         const bool wave_active = !CAUSAL || key0 <= wave_q0 + 32 * RQ - 1;
@@ -135,23 +139,40 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             f32x16 sacc[RQ][KT];
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
-#ifdef FA_SETPRIO
-            __builtin_amdgcn_s_setprio(1);
-#endif
+            if constexpr (PD > 0) {
+                // Operand reads run PD MFMA steps ahead of their use, and the scheduler may move only
+                // VALU / SALU work across a step: with one wave per SIMD nothing else hides LDS latency.
+                constexpr int NU = KS * KT;
+                constexpr int P0 = PD < NU ? PD : NU;
+                i32x4 abuf[P0];
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+                for (int u = 0; u < P0; ++u)
+                    abuf[u] = *reinterpret_cast<const i32x4*>(ks_base + (u % KT) * 32 * KSTR + (u / KT) * 16);
 #pragma unroll
-                for (int kt = 0; kt < KT; ++kt) {
-                    i32x4 a = *reinterpret_cast<const i32x4*>(ks_base + kt * 32 * KSTR + ks * 16);
+                for (int u = 0; u < NU; ++u) {
+                    const int ks = u / KT, kt = u % KT;
+                    i32x4 a = abuf[u % P0];
+                    if (u + P0 < NU)
+                        abuf[u % P0] = *reinterpret_cast<const i32x4*>(ks_base + ((u + P0) % KT) * 32 * KSTR +
+                                                                       ((u + P0) / KT) * 16);
 #pragma unroll
                     for (int rq = 0; rq < RQ; ++rq)
                         sacc[rq][kt] = E::mma(a, qreg[rq][ks], ks == 0 ? zero : sacc[rq][kt]);
+                    __builtin_amdgcn_sched_barrier(0x6);
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                    for (int kt = 0; kt < KT; ++kt) {
+                        i32x4 a = *reinterpret_cast<const i32x4*>(ks_base + kt * 32 * KSTR + ks * 16);
+#pragma unroll
+                        for (int rq = 0; rq < RQ; ++rq)
+                            sacc[rq][kt] = E::mma(a, qreg[rq][ks], ks == 0 ? zero : sacc[rq][kt]);
+                    }
                 }
             }
 
-#ifdef FA_SETPRIO
-            __builtin_amdgcn_s_setprio(0);
-#endif
             // ---- mask: keys past N, and keys after the query when causal
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
             if (need_mask) {
@@ -199,15 +220,8 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     float p[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-#if defined(FA_EXP_NOEXP)
-                        p[r] = __builtin_fmaf(sacc[rq][kt][r], sc, -mb);
-                        psum += p[r];
-#elif defined(FA_EXP_NOSOFTMAX)
-                        p[r] = sacc[rq][kt][r];
-#else
                         p[r] = fast_exp2(__builtin_fmaf(sacc[rq][kt][r], sc, -mb));
                         psum += p[r];
-#endif
                     }
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
@@ -222,33 +236,50 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 
             // ---- GEMM1: O^T += V_j^T P^T
             const uint16_t* vs_base = lds_v[st] + (4 * half + tr_row) * VSTR + tr_col;
+            if constexpr (PD > 0) {
+                constexpr int NU = SL * DT;
+                constexpr int P0 = PD < NU ? PD : NU;
+                i32x2 lo[P0], hi[P0];
 #pragma unroll
-            for (int sl = 0; sl < SL; ++sl) {
+                for (int u = 0; u < P0; ++u) {
+                    const uint16_t* p0 = vs_base + ((u / DT) * 16) * VSTR + (u % DT) * 32;
+                    lo[u] = lds_read_tr16(p0);
+                    hi[u] = lds_read_tr16(p0 + 8 * VSTR);
+                }
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-#ifdef FA_EXP_NOTR
-                    i32x4 a = *reinterpret_cast<const i32x4*>(reinterpret_cast<const char*>(lds_v[st]) + col * 272 + half * 16 + dt * 32 + sl * (BC * VSTR * 2 / SL / 16 * 16 - 640));
-#else
-                    const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
-                    i32x2 lo = lds_read_tr16(p0);
-                    i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
-                    i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
-#endif
+                for (int u = 0; u < NU; ++u) {
+                    const int sl = u / DT, dt = u % DT;
+                    i32x4 a = {lo[u % P0][0], lo[u % P0][1], hi[u % P0][0], hi[u % P0][1]};
+                    if (u + P0 < NU) {
+                        const uint16_t* p0 = vs_base + (((u + P0) / DT) * 16) * VSTR + ((u + P0) % DT) * 32;
+                        lo[u % P0] = lds_read_tr16(p0);
+                        hi[u % P0] = lds_read_tr16(p0 + 8 * VSTR);
+                    }
 #pragma unroll
                     for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
+                    __builtin_amdgcn_sched_barrier(0x6);
+                }
+            } else {
+#pragma unroll
+                for (int sl = 0; sl < SL; ++sl) {
+#pragma unroll
+                    for (int dt = 0; dt < DT; ++dt) {
+                        const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
+                        i32x2 lo = lds_read_tr16(p0);
+                        i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
+                        i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+#pragma unroll
+                        for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
+                    }
                 }
             }
         }
 
-#ifndef FA_EXP_NOSTAGE
         if (more) {
             Copy::template to_lds<KSTR>(lds_k[st ^ 1], tid, kpre);
             Copy::template to_lds<VSTR>(lds_v[st ^ 1], tid, vpre);
         }
-#endif
-#ifndef FA_EXP_NOBARRIER
         __syncthreads();
-#endif
     }
 
     // ---- epilogue: O / l, L = m + log l
@@ -344,7 +375,7 @@ __global__ void __launch_bounds__(64) fa_fwd_f32_kernel(const float* __restrict_
 }
 
 // ---------------------------------------------------------------------------------------
-template <typename Tag, int D, int BC, int NW, int RQ>
+template <typename Tag, int D, int BC, int NW, int RQ, int PD>
 static int launch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
                         float scale, int causal, hipStream_t stream) {
     constexpr int BR = NW * 32 * RQ;
@@ -357,30 +388,32 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
     auto vp = static_cast<const uint16_t*>(v);
     auto op = static_cast<uint16_t*>(o);
     if (causal)
-        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, true>), grid, block, 0, stream, qp, kp, vp, op,
-                           lse, N, n_qtiles, (int)total, scale);
+        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, PD, true>), grid, block, 0, stream, qp, kp, vp,
+                           op, lse, N, n_qtiles, (int)total, scale);
     else
-        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, false>), grid, block, 0, stream, qp, kp, vp, op,
-                           lse, N, n_qtiles, (int)total, scale);
+        hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, PD, false>), grid, block, 0, stream, qp, kp, vp,
+                           op, lse, N, n_qtiles, (int)total, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
+// Tile choice (measured on MI355X at the 16k-token benchmark shapes):
+//   d = 64, 128: eight waves share each K/V block (256 query rows per workgroup, two waves per
+//     SIMD), which halves the L2->LDS traffic per FLOP; short causal problems keep 128-row
+//     workgroups so that fewer waves idle on the diagonal.
+//   d = 256: the 128-register output accumulator allows only one wave per SIMD, so the operand
+//     reads are software-pipelined eight MFMA steps ahead instead.
 template <typename Tag>
 static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
                           int d, float scale, int causal, hipStream_t stream) {
+    const bool small_tile = causal ? (N <= 2048) : (N <= 512);
     switch (d) {
-        case 64: return launch_16bit<Tag, 64, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-        case 128: {
-            const char* e = getenv("FA_FWD_VARIANT");  // EXPERIMENT
-            int var = e ? atoi(e) : 0;
-            if (var == 1) return launch_16bit<Tag, 128, 64, 4, 2>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            if (var == 2) return launch_16bit<Tag, 128, 64, 8, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            if (var == 3) return launch_16bit<Tag, 128, 32, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            if (var == 4) return launch_16bit<Tag, 128, 128, 8, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            if (var == 5) return launch_16bit<Tag, 128, 32, 4, 2>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            return launch_16bit<Tag, 128, 64, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-        }
-        case 256: return launch_16bit<Tag, 256, 32, 4, 1>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 64:
+            if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 128:
+            if (small_tile) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            return launch_16bit<Tag, 128, 128, 8, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+        case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }

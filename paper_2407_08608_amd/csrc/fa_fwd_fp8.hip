@@ -13,14 +13,16 @@
 //     accumulator registers to operand registers with conversions only, no cross-lane moves.
 //     This is the same idea as the paper's register permutation plus matching V-row
 //     permutation, rederived for the gfx950 layouts.
-//   * P~ = exp2(s - m + 8): the bias uses more of e4m3's range (P~ <= 256 < 448) and cancels
-//     in O / l; L subtracts it again.
+//   * P~ = exp2(s - m_ref + 7) where the reference maximum m_ref is raised only when a block's
+//     maximum exceeds it by more than 1 (log2 units), so P~ <= 256 < 448: the bias uses more of
+//     e4m3's range, both factors cancel in O / l, and L subtracts the bias again.
 #include "fa_device.h"
 #include "fa_launch.h"
 
 namespace fa {
 
-constexpr float kPBias = 8.0f;
+constexpr float kPBias = 7.0f;
+constexpr float kLazyLog2 = 1.0f;
 
 static __device__ __forceinline__ f32x16 mma_fp8(i32x8 a, i32x8 b, f32x16 c) {
     // cbsz = blgp = 0: both operands e4m3; scale exponents 127 = 1.0
@@ -76,13 +78,12 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 
     i32x8 qreg[KS];
     {
-        int row = wave_q0 + col;
+        int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
-            i32x4 z = {0, 0, 0, 0};
             const uint8_t* p = qh + (size_t)row * D + ks * 64 + half * 32;
-            i32x4 lo = row < N ? *reinterpret_cast<const i32x4*>(p) : z;
-            i32x4 hi = row < N ? *reinterpret_cast<const i32x4*>(p + 16) : z;
+            i32x4 lo = *reinterpret_cast<const i32x4*>(p);
+            i32x4 hi = *reinterpret_cast<const i32x4*>(p + 16);
             qreg[ks] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         }
     }
@@ -98,15 +99,13 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
     int last_q = min(qt * BR + BR, N) - 1;
     int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
 
-    auto load_tile = [&](const uint8_t* head, int key0, i32x4 (&regs)[CPT]) {
+    // a [BC][D] tile of a row-major head is contiguous: chunk c sits at tile offset 16*c; rows past N
+    // lie outside the buffer resource and read as zero
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_buffer(kh, (uint32_t)N * D);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_buffer(vh, (uint32_t)N * D);
+    auto load_tile = [&](__amdgpu_buffer_rsrc_t head, int key0, i32x4 (&regs)[CPT]) {
 #pragma unroll
-        for (int i = 0; i < CPT; ++i) {
-            int c = tid + i * NT;
-            int row = c / CPR, cc = c % CPR;
-            int key = key0 + row;
-            i32x4 z = {0, 0, 0, 0};
-            regs[i] = key < N ? *reinterpret_cast<const i32x4*>(head + (size_t)key * D + cc * 16) : z;
-        }
+        for (int i = 0; i < CPT; ++i) regs[i] = buffer_load_16B(head, key0 * D + (tid + i * NT) * 16);
     };
     auto store_tile = [&](uint8_t* lds, int stride, const i32x4 (&regs)[CPT]) {
 #pragma unroll
@@ -118,10 +117,12 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
     };
 
     i32x4 kpre[CPT], vpre[CPT];
-    load_tile(kh, 0, kpre);
-    load_tile(vh, 0, vpre);
+    load_tile(k_rsrc, 0, kpre);
+    load_tile(v_rsrc, 0, vpre);
     store_tile(lds_k[0], KSTR, kpre);
     store_tile(lds_v[0], VSTR, vpre);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));  // Q loads complete before the loop
     __syncthreads();
 
     const int krow = key_of_row(col);  // key (within a 32-key tile) this lane's A row reads
@@ -133,8 +134,8 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         const int key0 = t * BC;
         const bool more = (t + 1 < n_blocks);
         if (more) {
-            load_tile(kh, key0 + BC, kpre);
-            load_tile(vh, key0 + BC, vpre);
+            load_tile(k_rsrc, key0 + BC, kpre);
+            load_tile(v_rsrc, key0 + BC, vpre);
         }
         const bool wave_active = !CAUSAL || key0 <= wave_q0 + 31;
         if (wave_active) {
@@ -147,10 +148,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 
             // ---- GEMM0: S^T = K_j Q_i^T (rows permuted by key_of_row)
             f32x16 sacc[KT];
-#pragma unroll
-            for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) sacc[kt][r] = 0.f;
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
@@ -159,7 +157,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     i32x4 lo = *reinterpret_cast<const i32x4*>(p);
                     i32x4 hi = *reinterpret_cast<const i32x4*>(p + 16);
                     i32x8 a = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    sacc[kt] = mma_fp8(a, qreg[ks], sacc[kt]);
+                    sacc[kt] = mma_fp8(a, qreg[ks], ks == 0 ? zero : sacc[kt]);
                 }
 
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
@@ -183,10 +181,22 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
             mx = max_both_halves(mx) * sc;
-            float m_new = fmaxf(m_run, mx);
-            float corr = fast_exp2(m_run - m_new);
-            m_run = m_new;
-            const float mb = m_new - kPBias;
+            const bool raise = mx - m_run > kLazyLog2;
+            const bool new_vscale = sv_new != sv_cur;
+            if (__builtin_amdgcn_ballot_w64(raise) != 0 || new_vscale) {
+                // rescale for a raised reference maximum and / or a new V block scale (the
+                // accumulator is kept in units of the current V block's scale)
+                float corr = raise ? fast_exp2(m_run - mx) : 1.0f;
+                m_run = raise ? mx : m_run;
+                l_run *= corr;
+                float f = corr * (sv_cur / sv_new);
+                sv_cur = sv_new;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
+            }
+            const float mb = m_run - kPBias;
             float psum = 0.f;
             i32x8 pb[SL];
 #pragma unroll
@@ -205,14 +215,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     pb[kt >> 1][4 * (kt & 1) + w] = word;
                 }
             }
-            l_run = l_run * corr + psum;
-            // accumulator changes units when the V block (and its scale) changes
-            float f = corr * (sv_cur / sv_new);
-            sv_cur = sv_new;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
+            l_run += psum;
 
             // ---- GEMM1: O^T += V_j^T P^T
             const uint8_t* vs_base = lds_v[st] + (8 * half + tr_row) * VSTR + tr_col;
@@ -285,9 +288,14 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
                    const float* v_scale, void* o, float* lse, int B, int H, int N, int d, float scale, int causal,
                    hipStream_t stream) {
+    const bool small_tile = causal ? (N <= 2048) : (N <= 512);
     switch (d) {
-        case 64: return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
-        case 128: return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+        case 64:
+            if (small_tile) return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+            return launch_fp8<64, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+        case 128:
+            if (small_tile) return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+            return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
         case 256: return launch_fp8<256, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
