@@ -21,6 +21,7 @@
 namespace fa {
 
 constexpr int kBwdD = 128;
+constexpr int kPipe = 4;  // MFMA steps by which LDS operand reads lead their use
 
 // ---------------------------------------------------------------------------------------
 template <typename Tag>
@@ -140,24 +141,25 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
     const int n_qtiles = (N + BQ - 1) / BQ;
     const int it0 = CAUSAL ? key0 / BQ : 0;  // first query tile that can see this key block
 
+    // Q_i and dO_i tiles are contiguous runs of the row-major tensors; rows past N lie outside the
+    // buffer resources and read as zero.
+    const __amdgpu_buffer_rsrc_t q_rsrc = make_buffer(qh, (uint32_t)N * D * 2);
+    const __amdgpu_buffer_rsrc_t do_rsrc = make_buffer(doh, (uint32_t)N * D * 2);
     i32x4 qpre[QCH], dopre[QCH];
     float lpre = 0.f;  // threads 0..63 carry L, 64..127 carry D
     auto load_tile = [&](int it) {
         const int q0 = it * BQ;
 #pragma unroll
         for (int i = 0; i < QCH; ++i) {
-            int c = tid + i * NT;
-            int row = c / CPR, cc = c % CPR;
-            i32x4 z = {0, 0, 0, 0};
-            bool ok = q0 + row < N;
-            qpre[i] = ok ? *reinterpret_cast<const i32x4*>(qh + (size_t)(q0 + row) * D + cc * 8) : z;
-            dopre[i] = ok ? *reinterpret_cast<const i32x4*>(doh + (size_t)(q0 + row) * D + cc * 8) : z;
+            qpre[i] = buffer_load_16B(q_rsrc, q0 * D * 2 + (tid + i * NT) * 16);
+            dopre[i] = buffer_load_16B(do_rsrc, q0 * D * 2 + (tid + i * NT) * 16);
         }
-        if (tid < BQ) {
-            // rows past N get L = +inf so that P = exp2(0 - inf) = 0
-            lpre = q0 + tid < N ? lh[q0 + tid] * kLog2e : INFINITY;
-        } else if (tid < 2 * BQ) {
-            lpre = q0 + tid - BQ < N ? dh[q0 + tid - BQ] : 0.f;
+        if (tid < 2 * BQ) {
+            const int r = q0 + (tid & (BQ - 1));
+            const float* src = tid < BQ ? lh : dh;
+            float x = src[min(r, N - 1)];
+            // rows past N get L = +inf so that P = exp2(0 - inf) = 0, and D = 0
+            lpre = tid < BQ ? (r < N ? x * kLog2e : INFINITY) : (r < N ? x : 0.f);
         }
     };
     auto store_tile = [&](int st) {
@@ -188,23 +190,40 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
         if (more) load_tile(it + 1);
 
         i32x4 pa[2][2], dsa[2][2];  // [query sub-tile][16-query slab]: P^T and dS^T as A operands
+        const bool need_mask = key0 + BK > N || (CAUSAL && key0 + BK - 1 > q0);
+
+        // ---- S = Q_i K_j^T and dP = dO_i V_j^T for both 32-query sub-tiles.  With one wave per SIMD
+        // nothing else hides LDS latency, so operand reads run kPipe steps ahead of the MFMAs.
+        f32x16 sacc[2], pacc[2];
+        {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            constexpr int NU = 2 * KS;
+            const uint16_t* qrow = lds_q[st] + col * RSTR + half * 8;
+            const uint16_t* dorow = lds_do[st] + col * RSTR + half * 8;
+            i32x4 aq[kPipe], ado[kPipe];
+#pragma unroll
+            for (int u = 0; u < kPipe; ++u) {
+                aq[u] = *reinterpret_cast<const i32x4*>(qrow + (u / KS) * 32 * RSTR + (u % KS) * 16);
+                ado[u] = *reinterpret_cast<const i32x4*>(dorow + (u / KS) * 32 * RSTR + (u % KS) * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int sub = u / KS, ks = u % KS;
+                i32x4 a0 = aq[u % kPipe], a1 = ado[u % kPipe];
+                if (u + kPipe < NU) {
+                    const int v = u + kPipe;
+                    aq[u % kPipe] = *reinterpret_cast<const i32x4*>(qrow + (v / KS) * 32 * RSTR + (v % KS) * 16);
+                    ado[u % kPipe] = *reinterpret_cast<const i32x4*>(dorow + (v / KS) * 32 * RSTR + (v % KS) * 16);
+                }
+                sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
+                pacc[sub] = E::mma(a1, vreg[ks], ks == 0 ? zero : pacc[sub]);
+                __builtin_amdgcn_sched_barrier(0x6);  // only VALU / SALU may move across a step
+            }
+        }
+
+        // ---- P = exp(S - L), dS = P o (dP - D); pack as A operands; dS^T to LDS
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
-            f32x16 sacc, pacc;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                sacc[r] = 0.f;
-                pacc[r] = 0.f;
-            }
-            const uint16_t* qrow = lds_q[st] + (sub * 32 + col) * RSTR + half * 8;
-            const uint16_t* dorow = lds_do[st] + (sub * 32 + col) * RSTR + half * 8;
-#pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
-                i32x4 aq = *reinterpret_cast<const i32x4*>(qrow + ks * 16);
-                i32x4 ado = *reinterpret_cast<const i32x4*>(dorow + ks * 16);
-                sacc = E::mma(aq, kreg[ks], sacc);   // S  = Q_i K_j^T
-                pacc = E::mma(ado, vreg[ks], pacc);  // dP = dO_i V_j^T
-            }
             float pv[16], dsv[16];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -213,11 +232,13 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
                 f32x4 d4 = *reinterpret_cast<const f32x4*>(&lds_d[st][ql]);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    float p = fast_exp2(__builtin_fmaf(sacc[4 * g + r], sc, -l4[r]));
-                    bool masked = my_key >= N || (CAUSAL && my_key > q0 + ql + r);
-                    p = masked ? 0.f : p;
+                    float p = fast_exp2(__builtin_fmaf(sacc[sub][4 * g + r], sc, -l4[r]));
+                    if (need_mask) {
+                        bool masked = my_key >= N || (CAUSAL && my_key > q0 + ql + r);
+                        p = masked ? 0.f : p;
+                    }
                     pv[4 * g + r] = p;
-                    dsv[4 * g + r] = p * (pacc[4 * g + r] - d4[r]);
+                    dsv[4 * g + r] = p * (pacc[sub][4 * g + r] - d4[r]);
                 }
             }
 #pragma unroll
@@ -228,7 +249,7 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
                     dsa[sub][s2][e] = E::pack2(dsv[8 * s2 + 2 * e], dsv[8 * s2 + 2 * e + 1]);
                 }
             }
-            // dS^T to LDS: row = this lane's key, 4 consecutive queries per group
+            // row = this lane's key, 4 consecutive queries per group
             uint16_t* dsrow = lds_ds + (wave * 32 + col) * SSTR + sub * 32 + 4 * half;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -238,44 +259,67 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
         }
 
         // ---- dV_j += P^T dO_i,  dK_j += dS^T Q_i   (contract over the tile's queries)
+        {
+            constexpr int NU = 2 * 2 * DT;  // (sub, slab, d-tile)
+            const int rbase = (4 * half + tr_row) * RSTR + tr_col;
+            auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + (u % DT) * 32; };
+            i32x2 dlo[kPipe], dhi[kPipe], qlo[kPipe], qhi[kPipe];
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                const int r0 = (sub * 32 + s2 * 16 + 4 * half + tr_row) * RSTR + tr_col;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    i32x2 lo = lds_read_tr16(lds_do[st] + r0 + dt * 32);
-                    i32x2 hi = lds_read_tr16(lds_do[st] + r0 + 8 * RSTR + dt * 32);
-                    i32x4 b = {lo[0], lo[1], hi[0], hi[1]};
-                    dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
-                    lo = lds_read_tr16(lds_q[st] + r0 + dt * 32);
-                    hi = lds_read_tr16(lds_q[st] + r0 + 8 * RSTR + dt * 32);
-                    i32x4 b2 = {lo[0], lo[1], hi[0], hi[1]};
-                    dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
-                }
+            for (int u = 0; u < kPipe; ++u) {
+                dlo[u] = lds_read_tr16(lds_do[st] + off(u));
+                dhi[u] = lds_read_tr16(lds_do[st] + off(u) + 8 * RSTR);
+                qlo[u] = lds_read_tr16(lds_q[st] + off(u));
+                qhi[u] = lds_read_tr16(lds_q[st] + off(u) + 8 * RSTR);
             }
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int sub = u / (2 * DT), s2 = (u / DT) % 2, dt = u % DT;
+                const int w = u % kPipe;
+                i32x4 b = {dlo[w][0], dlo[w][1], dhi[w][0], dhi[w][1]};
+                i32x4 b2 = {qlo[w][0], qlo[w][1], qhi[w][0], qhi[w][1]};
+                if (u + kPipe < NU) {
+                    dlo[w] = lds_read_tr16(lds_do[st] + off(u + kPipe));
+                    dhi[w] = lds_read_tr16(lds_do[st] + off(u + kPipe) + 8 * RSTR);
+                    qlo[w] = lds_read_tr16(lds_q[st] + off(u + kPipe));
+                    qhi[w] = lds_read_tr16(lds_q[st] + off(u + kPipe) + 8 * RSTR);
+                }
+                dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
+                dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
+                __builtin_amdgcn_sched_barrier(0x6);
+            }
+        }
 
         __syncthreads();  // dS^T of all four waves is in LDS
 
         // ---- dQ_i += dS K_j: this wave produces head-dim columns 32w..32w+31 of both sub-tiles
         f32x16 dqacc[2];
+        {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            constexpr int NU = BK / 16;
+            constexpr int PD = kPipe < NU ? kPipe : NU;
+            const int kb0 = (4 * half + tr_row) * RSTR + wave * 32 + tr_col;
+            const int sb0 = (4 * half + tr_row) * SSTR + tr_col;
+            i32x2 blo[PD], bhi[PD], a0lo[PD], a0hi[PD], a1lo[PD], a1hi[PD];
+            auto load = [&](int w, int s) {
+                blo[w] = lds_read_tr16(lds_k + kb0 + 16 * s * RSTR);
+                bhi[w] = lds_read_tr16(lds_k + kb0 + (16 * s + 8) * RSTR);
+                a0lo[w] = lds_read_tr16(lds_ds + sb0 + 16 * s * SSTR);
+                a0hi[w] = lds_read_tr16(lds_ds + sb0 + (16 * s + 8) * SSTR);
+                a1lo[w] = lds_read_tr16(lds_ds + sb0 + 16 * s * SSTR + 32);
+                a1hi[w] = lds_read_tr16(lds_ds + sb0 + (16 * s + 8) * SSTR + 32);
+            };
 #pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
+            for (int u = 0; u < PD; ++u) load(u, u);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) dqacc[sub][r] = 0.f;
-#pragma unroll
-        for (int s = 0; s < BK / 16; ++s) {
-            const int krow0 = 16 * s + 4 * half + tr_row;
-            i32x2 lo = lds_read_tr16(lds_k + krow0 * RSTR + wave * 32 + tr_col);
-            i32x2 hi = lds_read_tr16(lds_k + (krow0 + 8) * RSTR + wave * 32 + tr_col);
-            i32x4 b = {lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-            for (int sub = 0; sub < 2; ++sub) {
-                i32x2 alo = lds_read_tr16(lds_ds + krow0 * SSTR + sub * 32 + tr_col);
-                i32x2 ahi = lds_read_tr16(lds_ds + (krow0 + 8) * SSTR + sub * 32 + tr_col);
-                i32x4 a = {alo[0], alo[1], ahi[0], ahi[1]};
-                dqacc[sub] = E::mma(a, b, dqacc[sub]);
+            for (int u = 0; u < NU; ++u) {
+                const int w = u % PD;
+                i32x4 b = {blo[w][0], blo[w][1], bhi[w][0], bhi[w][1]};
+                i32x4 a0 = {a0lo[w][0], a0lo[w][1], a0hi[w][0], a0hi[w][1]};
+                i32x4 a1 = {a1lo[w][0], a1lo[w][1], a1hi[w][0], a1hi[w][1]};
+                if (u + PD < NU) load(w, u + PD);
+                dqacc[0] = E::mma(a0, b, u == 0 ? zero : dqacc[0]);
+                dqacc[1] = E::mma(a1, b, u == 0 ? zero : dqacc[1]);
+                __builtin_amdgcn_sched_barrier(0x6);
             }
         }
 #pragma unroll
@@ -283,7 +327,11 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 int qi = q0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+#ifdef FA_EXP_NOATOMIC
+                if (qi < N && dqacc[sub][r] == 123.456f) dqh[(size_t)qi * D + wave * 32 + col] = dqacc[sub][r];
+#else
                 if (qi < N) unsafeAtomicAdd(dqh + (size_t)qi * D + wave * 32 + col, dqacc[sub][r]);
+#endif
             }
 
         if (more) store_tile(st ^ 1);
