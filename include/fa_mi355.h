@@ -103,15 +103,15 @@ int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales,
                           const signed char* signs, int per_tensor, void* stream);
 
 /*
- * Backward pass (section 2.1 chain rule; Algorithm 3):
+ * Backward pass (section 2.1 chain rule; recomputation of P from L as in Algorithm 3):
  *     D = rowsum(dO o O);  P = exp(S - L);  dV = P^T dO;  dP = dO V^T;
  *     dS = P o (dP - D);   dQ = scale * dS K;   dK = scale * dS^T Q.
  *   q, k, v, o, dout : [B,H,N,d] of `dtype`; lse : fp32 [B,H,N] from fa_fwd   (device, read)
  *   dq, dk, dv       : [B,H,N,d] of `dtype`                                   (device, written)
- *   workspace        : device scratch of at least fa_bwd_workspace_bytes(...) bytes,
+ *   workspace        : device scratch of at least fa_bwd_workspace_bytes(...) bytes (it holds D),
  *                      16-byte aligned, owned by the caller, contents undefined on return.
- * dtype FA_BF16 or FA_F16; d = 128 only (others: FA_ERR_UNSUPPORTED).  dQ is accumulated
- * with fp32 atomics, so its low-order bits may differ from run to run.
+ * dtype FA_BF16 or FA_F16; d = 128 only (others: FA_ERR_UNSUPPORTED).  Nothing is accumulated
+ * with atomics: results are bit-for-bit repeatable.
  */
 size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype);
 

@@ -1,20 +1,25 @@
-// Backward attention for gfx950, head dimension 128, bf16 / fp16 (paper Algorithm 3).
+// Backward attention for gfx950, head dimension 128, bf16 / fp16 (paper section 2.1 chain rule,
+// Algorithm 3's recomputation of P from L and its D = rowsum(dO o O)).
 //
-//   preprocess : D = rowsum(dO o O) per query row, and the fp32 dQ accumulator is cleared
-//   main       : one workgroup per block of 128 keys (wave w owns keys 32w..32w+31); loop over
-//                tiles of 64 queries:  S = Q_i K_j^T,  dP = dO_i V_j^T,  P = exp(S - L),
-//                dS = P o (dP - D),  dV_j += P^T dO_i,  dK_j += dS^T Q_i  (on chip),
-//                dQ_i += dS K_j  (fp32 atomics into the accumulator, as in the paper)
-//   convert    : dQ = scale * accumulator, cast to the I/O dtype
+//   preprocess : D = rowsum(dO o O) per query row (HBM-bound)
+//   dK/dV pass : one workgroup per block of 128 keys (wave w owns keys 32w..32w+31 and keeps
+//                dK_j, dV_j on chip); loop over tiles of 64 queries:
+//                S = Q_i K_j^T, dP = dO_i V_j^T, P = exp(S - L), dS = P o (dP - D),
+//                dV_j += P^T dO_i, dK_j += dS^T Q_i
+//   dQ pass    : one workgroup per tile of queries (dQ_i on chip), loop over key blocks:
+//                S^T = K_j Q_i^T, dP^T = V_j dO_i^T, P, dS as above, dQ_i^T += K_j^T dS^T
 //
-// Register layouts: S and dP are computed with queries as MFMA rows and keys as columns, so a
-// lane owns one key and 16 queries in its accumulator registers; packed to 16 bits those
-// registers are directly the A operand (keys x queries) of the dV and dK products, whose B
-// operands (dO, Q as queries x d) come from transposing LDS reads.  dQ contracts over keys,
-// which lanes do not own, so dS^T goes through LDS once (written [key][query], read back with
-// transposing reads) -- the role the dQ staging buffer and writer warp play in Algorithm 3.
-#include <hip/amd_detail/amd_hip_unsafe_atomics.h>
-
+// Algorithm 3 produces dQ inside the dK/dV loop and adds it to HBM with atomics.  Measured on
+// MI355X that accumulation (17 GB of fp32 atomic traffic at seqlen 16k) cost about 30 % of the
+// pass, so dQ gets its own pass instead: two of the five GEMMs are recomputed, nothing is
+// accumulated in HBM, no fp32 dQ buffer or cast pass exists, and the result is deterministic.
+//
+// Register layouts.  dK/dV pass: S and dP have queries as MFMA rows and keys as columns, so a
+// lane owns one key and 16 queries; packed to 16 bits those registers are directly the A
+// operand (keys x queries) of the dV and dK products, whose B operands (dO, Q as queries x d)
+// come from transposing LDS reads.  dQ pass: the forward kernel's layout -- S^T and dP^T have
+// one query per lane column, dS^T packs straight into the B operand of dQ^T += K^T dS^T, and
+// K^T is the transposing read of the same LDS tile that fed S^T.
 #include "fa_device.h"
 #include "fa_launch.h"
 
@@ -27,7 +32,7 @@ constexpr int kPipe = 4;  // MFMA steps by which LDS operand reads lead their us
 template <typename Tag>
 __global__ void __launch_bounds__(256)
 fa_bwd_preprocess_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dout,
-                         float* __restrict__ dvec, float* __restrict__ dq_acc, long rows) {
+                         float* __restrict__ dvec, long rows) {
     constexpr int D = kBwdD;
     using E = Elem<Tag>;
     const int lane16 = threadIdx.x & 15;
@@ -42,52 +47,32 @@ fa_bwd_preprocess_kernel(const uint16_t* __restrict__ o, const uint16_t* __restr
             acc = __builtin_fmaf(E::to_float((uint16_t)(ua & 0xFFFF)), E::to_float((uint16_t)(ub & 0xFFFF)), acc);
             acc = __builtin_fmaf(E::to_float((uint16_t)(ua >> 16)), E::to_float((uint16_t)(ub >> 16)), acc);
         }
-        f32x4 z = {0.f, 0.f, 0.f, 0.f};
-        *reinterpret_cast<f32x4*>(dq_acc + row * D + lane16 * 8) = z;
-        *reinterpret_cast<f32x4*>(dq_acc + row * D + lane16 * 8 + 4) = z;
     }
 #pragma unroll
     for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (row < rows && lane16 == 0) dvec[row] = acc;
 }
 
-template <typename Tag>
-__global__ void __launch_bounds__(256)
-fa_bwd_convert_dq_kernel(const float* __restrict__ dq_acc, uint16_t* __restrict__ dq, long n8, float scale) {
-    using E = Elem<Tag>;
-    long i = (long)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n8) return;
-    f32x4 a = *reinterpret_cast<const f32x4*>(dq_acc + i * 8);
-    f32x4 b = *reinterpret_cast<const f32x4*>(dq_acc + i * 8 + 4);
-    i32x4 w = {E::pack2(a[0] * scale, a[1] * scale), E::pack2(a[2] * scale, a[3] * scale),
-               E::pack2(b[0] * scale, b[1] * scale), E::pack2(b[2] * scale, b[3] * scale)};
-    *reinterpret_cast<i32x4*>(dq + i * 8) = w;
-}
-
 // ---------------------------------------------------------------------------------------
 template <typename Tag, bool CAUSAL>
 __global__ void __launch_bounds__(256, 1)
-fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
               const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
-              float* __restrict__ dq_acc, uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
+              uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
               int n_kblocks, int total_wg, float scale) {
     constexpr int D = kBwdD;
     constexpr int BK = 128;        // keys per workgroup
     constexpr int BQ = 64;         // queries per loop iteration
     constexpr int NT = 256;
     constexpr int RSTR = D + 8;    // row stride (elements) of the Q, dO and K tiles
-    constexpr int SSTR = BQ + 8;   // row stride of the dS^T tile [key][query]
     constexpr int KS = D / 16;
     constexpr int DT = D / 32;
     constexpr int CPR = D / 8;     // 16-byte chunks per row
     constexpr int QCH = BQ * CPR / NT;  // chunks per thread for a Q / dO tile
-    constexpr int KCH = BK * CPR / NT;
     using E = Elem<Tag>;
 
     __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][BQ * RSTR];
     __shared__ __attribute__((aligned(16))) uint16_t lds_do[2][BQ * RSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_k[BK * RSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_ds[BK * SSTR];
     __shared__ __attribute__((aligned(16))) float lds_l[2][BQ];
     __shared__ __attribute__((aligned(16))) float lds_d[2][BQ];
 
@@ -107,7 +92,6 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
     const uint16_t* doh = dout + head_off;
     const float* lh = lse + (size_t)bh * N;
     const float* dh = dvec + (size_t)bh * N;
-    float* dqh = dq_acc + head_off;
     const float sc = scale * kLog2e;
 
     // ---- this wave's K and V rows as B operands (lane: key column, 8 head-dim elements)
@@ -119,16 +103,6 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
         kreg[ks] = my_key < N ? *reinterpret_cast<const i32x4*>(kh + (size_t)my_key * D + ks * 16 + half * 8) : z;
         vreg[ks] = my_key < N ? *reinterpret_cast<const i32x4*>(vh + (size_t)my_key * D + ks * 16 + half * 8) : z;
     }
-    // ---- the whole K block in LDS for the dQ product
-#pragma unroll
-    for (int i = 0; i < KCH; ++i) {
-        int c = tid + i * NT;
-        int row = c / CPR, cc = c % CPR;
-        i32x4 z = {0, 0, 0, 0};
-        i32x4 w = key0 + row < N ? *reinterpret_cast<const i32x4*>(kh + (size_t)(key0 + row) * D + cc * 8) : z;
-        *reinterpret_cast<i32x4*>(lds_k + row * RSTR + cc * 8) = w;
-    }
-
     f32x16 dkacc[DT], dvacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -221,7 +195,7 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
             }
         }
 
-        // ---- P = exp(S - L), dS = P o (dP - D); pack as A operands; dS^T to LDS
+        // ---- P = exp(S - L), dS = P o (dP - D); pack as A operands
 #pragma unroll
         for (int sub = 0; sub < 2; ++sub) {
             float pv[16], dsv[16];
@@ -248,13 +222,6 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
                     pa[sub][s2][e] = E::pack2(pv[8 * s2 + 2 * e], pv[8 * s2 + 2 * e + 1]);
                     dsa[sub][s2][e] = E::pack2(dsv[8 * s2 + 2 * e], dsv[8 * s2 + 2 * e + 1]);
                 }
-            }
-            // row = this lane's key, 4 consecutive queries per group
-            uint16_t* dsrow = lds_ds + (wave * 32 + col) * SSTR + sub * 32 + 4 * half;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                i32x2 w = {dsa[sub][g >> 1][2 * (g & 1)], dsa[sub][g >> 1][2 * (g & 1) + 1]};
-                *reinterpret_cast<i32x2*>(dsrow + 8 * g) = w;
             }
         }
 
@@ -289,51 +256,6 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
             }
         }
 
-        __syncthreads();  // dS^T of all four waves is in LDS
-
-        // ---- dQ_i += dS K_j: this wave produces head-dim columns 32w..32w+31 of both sub-tiles
-        f32x16 dqacc[2];
-        {
-            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            constexpr int NU = BK / 16;
-            constexpr int PD = kPipe < NU ? kPipe : NU;
-            const int kb0 = (4 * half + tr_row) * RSTR + wave * 32 + tr_col;
-            const int sb0 = (4 * half + tr_row) * SSTR + tr_col;
-            i32x2 blo[PD], bhi[PD], a0lo[PD], a0hi[PD], a1lo[PD], a1hi[PD];
-            auto load = [&](int w, int s) {
-                blo[w] = lds_read_tr16(lds_k + kb0 + 16 * s * RSTR);
-                bhi[w] = lds_read_tr16(lds_k + kb0 + (16 * s + 8) * RSTR);
-                a0lo[w] = lds_read_tr16(lds_ds + sb0 + 16 * s * SSTR);
-                a0hi[w] = lds_read_tr16(lds_ds + sb0 + (16 * s + 8) * SSTR);
-                a1lo[w] = lds_read_tr16(lds_ds + sb0 + 16 * s * SSTR + 32);
-                a1hi[w] = lds_read_tr16(lds_ds + sb0 + (16 * s + 8) * SSTR + 32);
-            };
-#pragma unroll
-            for (int u = 0; u < PD; ++u) load(u, u);
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int w = u % PD;
-                i32x4 b = {blo[w][0], blo[w][1], bhi[w][0], bhi[w][1]};
-                i32x4 a0 = {a0lo[w][0], a0lo[w][1], a0hi[w][0], a0hi[w][1]};
-                i32x4 a1 = {a1lo[w][0], a1lo[w][1], a1hi[w][0], a1hi[w][1]};
-                if (u + PD < NU) load(w, u + PD);
-                dqacc[0] = E::mma(a0, b, u == 0 ? zero : dqacc[0]);
-                dqacc[1] = E::mma(a1, b, u == 0 ? zero : dqacc[1]);
-                __builtin_amdgcn_sched_barrier(0x6);
-            }
-        }
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                int qi = q0 + sub * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-#ifdef FA_EXP_NOATOMIC
-                if (qi < N && dqacc[sub][r] == 123.456f) dqh[(size_t)qi * D + wave * 32 + col] = dqacc[sub][r];
-#else
-                if (qi < N) unsafeAtomicAdd(dqh + (size_t)qi * D + wave * 32 + col, dqacc[sub][r]);
-#endif
-            }
-
         if (more) store_tile(st ^ 1);
         __syncthreads();
     }
@@ -353,39 +275,211 @@ fa_bwd_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, co
 }
 
 // ---------------------------------------------------------------------------------------
+// dQ pass: the forward kernel's structure with dO alongside Q and K^T in place of V^T.
+template <typename Tag, int BC, int NW, bool CAUSAL>
+__global__ void __launch_bounds__(NW * 64, 2)
+fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                 const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
+                 uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, float scale) {
+    constexpr int D = kBwdD;
+    constexpr int NT = NW * 64;
+    constexpr int BR = NW * 32;
+    constexpr int RSTR = D + 8;
+    constexpr int KT = BC / 32;
+    constexpr int KS = D / 16;
+    constexpr int DT = D / 32;
+    constexpr int SL = BC / 16;
+    constexpr int CPR = D / 8;
+    constexpr int CPT = BC * CPR / NT;
+    static_assert((BC * CPR) % NT == 0, "tile must divide evenly over the workgroup");
+    using E = Elem<Tag>;
+
+    __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][BC * RSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][BC * RSTR];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int bh = id / n_qtiles;
+    int qt = id % n_qtiles;
+    if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint16_t* kh = k + head_off;
+    const uint16_t* vh = v + head_off;
+    const int wave_q0 = qt * BR + wave * 32;
+    const int qi = wave_q0 + col;
+    const int qrow = min(qi, N - 1);  // rows past N compute a copy of row N-1, never stored
+    const float sc = scale * kLog2e;
+
+    i32x4 qreg[KS], doreg[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        qreg[ks] = *reinterpret_cast<const i32x4*>(q + head_off + (size_t)qrow * D + ks * 16 + half * 8);
+        doreg[ks] = *reinterpret_cast<const i32x4*>(dout + head_off + (size_t)qrow * D + ks * 16 + half * 8);
+    }
+    const float l2 = lse[(size_t)bh * N + qrow] * kLog2e;
+    const float dq_row = dvec[(size_t)bh * N + qrow];
+
+    f32x16 acc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[dt][r] = 0.f;
+
+    int last_q = min(qt * BR + BR, N) - 1;
+    int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_buffer(kh, (uint32_t)N * D * 2);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_buffer(vh, (uint32_t)N * D * 2);
+    i32x4 kpre[CPT], vpre[CPT];
+    auto load_tile = [&](int key0) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            kpre[i] = buffer_load_16B(k_rsrc, key0 * D * 2 + (tid + i * NT) * 16);
+            vpre[i] = buffer_load_16B(v_rsrc, key0 * D * 2 + (tid + i * NT) * 16);
+        }
+    };
+    auto store_tile = [&](int st) {
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) {
+            int c = tid + i * NT;
+            int row = c / CPR, cc = c % CPR;
+            *reinterpret_cast<i32x4*>(lds_k[st] + row * RSTR + cc * 8) = kpre[i];
+            *reinterpret_cast<i32x4*>(lds_v[st] + row * RSTR + cc * 8) = vpre[i];
+        }
+    };
+    load_tile(0);
+    store_tile(0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]), "+v"(doreg[ks]));  // loads done before the loop
+    __syncthreads();
+
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+    for (int t = 0; t < n_blocks; ++t) {
+        const int st = t & 1;
+        const int key0 = t * BC;
+        const bool more = (t + 1 < n_blocks);
+        if (more) load_tile(key0 + BC);
+
+        const bool wave_active = !CAUSAL || key0 <= wave_q0 + 31;
+        if (wave_active) {
+            // ---- S^T = K_j Q_i^T and dP^T = V_j dO_i^T
+            f32x16 sacc[KT], pacc[KT];
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            const int rbase = col * RSTR + half * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt) {
+                    i32x4 ak = *reinterpret_cast<const i32x4*>(lds_k[st] + rbase + kt * 32 * RSTR + ks * 16);
+                    i32x4 av = *reinterpret_cast<const i32x4*>(lds_v[st] + rbase + kt * 32 * RSTR + ks * 16);
+                    sacc[kt] = E::mma(ak, qreg[ks], ks == 0 ? zero : sacc[kt]);
+                    pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? zero : pacc[kt]);
+                }
+
+            // ---- P = exp(S - L), dS = P o (dP - D), packed as the B operand of the dQ product
+            const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
+            const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+            i32x4 dsb[SL];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt) {
+                float ds[16];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float p = fast_exp2(__builtin_fmaf(sacc[kt][r], sc, -l2));
+                    if (need_mask) {
+                        int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                        p = key > limit ? 0.f : p;
+                    }
+                    ds[r] = p * (pacc[kt][r] - dq_row);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    i32x4 w;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) w[e] = E::pack2(ds[8 * s2 + 2 * e], ds[8 * s2 + 2 * e + 1]);
+                    dsb[2 * kt + s2] = w;
+                }
+            }
+
+            // ---- dQ_i^T += K_j^T dS^T
+            const uint16_t* kt_base = lds_k[st] + (4 * half + tr_row) * RSTR + tr_col;
+#pragma unroll
+            for (int sl = 0; sl < SL; ++sl)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const uint16_t* p0 = kt_base + (sl * 16) * RSTR + dt * 32;
+                    i32x2 lo = lds_read_tr16(p0);
+                    i32x2 hi = lds_read_tr16(p0 + 8 * RSTR);
+                    i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+                    acc[dt] = E::mma(a, dsb[sl], acc[dt]);
+                }
+        }
+
+        if (more) store_tile(st ^ 1);
+        __syncthreads();
+    }
+
+    if (qi < N) {
+        uint16_t* row = dq + head_off + (size_t)qi * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                i32x2 w;
+                w[0] = E::pack2(acc[dt][4 * g] * scale, acc[dt][4 * g + 1] * scale);
+                w[1] = E::pack2(acc[dt][4 * g + 2] * scale, acc[dt][4 * g + 3] * scale);
+                *reinterpret_cast<i32x2*>(row + dt * 32 + 8 * g + 4 * half) = w;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 size_t bwd_workspace_bytes(int B, int H, int N, int d) {
+    (void)d;
     size_t rows = (size_t)B * H * N;
-    return rows * d * sizeof(float) + ((rows * sizeof(float) + 15) & ~(size_t)15);
+    return (rows * sizeof(float) + 15) & ~(size_t)15;  // D = rowsum(dO o O)
 }
 
 template <typename Tag>
 static int launch_bwd_t(const void* q, const void* k, const void* v, const void* o, const float* lse,
                         const void* dout, void* dq, void* dk, void* dv, void* workspace, int B, int H, int N,
                         float scale, int causal, hipStream_t stream) {
-    constexpr int D = kBwdD;
     const long rows = (long)B * H * N;
-    float* dq_acc = static_cast<float*>(workspace);
-    float* dvec = dq_acc + (size_t)rows * D;
+    float* dvec = static_cast<float*>(workspace);
     auto u16 = [](const void* p) { return static_cast<const uint16_t*>(p); };
 
     hipLaunchKernelGGL((fa_bwd_preprocess_kernel<Tag>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream,
-                       u16(o), u16(dout), dvec, dq_acc, rows);
+                       u16(o), u16(dout), dvec, rows);
 
     int n_kblocks = (N + 127) / 128;
     long total = (long)B * H * n_kblocks;
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     if (causal)
-        hipLaunchKernelGGL((fa_bwd_kernel<Tag, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q), u16(k),
-                           u16(v), u16(dout), lse, dvec, dq_acc, static_cast<uint16_t*>(dk),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+                           u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, scale);
     else
-        hipLaunchKernelGGL((fa_bwd_kernel<Tag, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q), u16(k),
-                           u16(v), u16(dout), lse, dvec, dq_acc, static_cast<uint16_t*>(dk),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+                           u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, scale);
 
-    long n8 = rows * D / 8;
-    hipLaunchKernelGGL((fa_bwd_convert_dq_kernel<Tag>), dim3((unsigned)((n8 + 255) / 256)), dim3(256), 0, stream,
-                       dq_acc, static_cast<uint16_t*>(dq), n8, scale);
+    constexpr int BC = 64, NW = 8;
+    int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
+    long total_q = (long)B * H * n_qtiles;
+    if (causal)
+        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, true>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
+                           u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
+                           (int)total_q, scale);
+    else
+        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, false>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
+                           u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
+                           (int)total_q, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
