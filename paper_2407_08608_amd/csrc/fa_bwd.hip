@@ -20,13 +20,15 @@
 // come from transposing LDS reads.  dQ pass: the forward kernel's layout -- S^T and dP^T have
 // one query per lane column, dS^T packs straight into the B operand of dQ^T += K^T dS^T, and
 // K^T is the transposing read of the same LDS tile that fed S^T.
+#include <type_traits>
+
 #include "fa_device.h"
 #include "fa_launch.h"
 
 namespace fa {
 
 constexpr int kBwdD = 128;
-constexpr int kPipe = 4;  // MFMA steps by which LDS operand reads lead their use
+constexpr int kPipe = 2;  // MFMA steps by which LDS operand reads lead their use
 
 // ---------------------------------------------------------------------------------------
 template <typename Tag>
@@ -64,7 +66,10 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     constexpr int BK = 128;        // keys per workgroup
     constexpr int BQ = 64;         // queries per loop iteration
     constexpr int NT = 256;
-    constexpr int RSTR = D + 8;    // row stride (elements) of the Q, dO and K tiles
+    // Row stride of the Q and dO tiles: they are read both as rows (128-bit) and transposed.
+    // Measured LDS rates per CU: 304 B gives 211 / 123 B/clk (rows / transposed), 272 B gives
+    // 208 / 63, 320 B gives 63 / 208.
+    constexpr int RSTR = D + 24;
     constexpr int KS = D / 16;
     constexpr int DT = D / 32;
     constexpr int CPR = D / 8;     // 16-byte chunks per row
@@ -103,6 +108,13 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         kreg[ks] = my_key < N ? *reinterpret_cast<const i32x4*>(kh + (size_t)my_key * D + ks * 16 + half * 8) : z;
         vreg[ks] = my_key < N ? *reinterpret_cast<const i32x4*>(vh + (size_t)my_key * D + ks * 16 + half * 8) : z;
     }
+    // The kernel needs more than 256 registers per lane, so part of them live in the accumulation
+    // half of the register file, which only MFMA can address directly.  K_j / V_j operands and the
+    // dK / dV accumulators are touched by MFMA alone: pin the operands there so that the score
+    // tiles, which the exponentials read, stay in ordinary registers and need no copies.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(kreg[ks]), "+a"(vreg[ks]));
+
     f32x16 dkacc[DT], dvacc[DT];
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
@@ -157,108 +169,136 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     const int tr_row = (lane & 15) >> 2;
     const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    for (int it = it0; it < n_qtiles; ++it) {
+    // Masked query tiles come first: every tile when the key block is ragged (keys past N), else
+    // the tiles on the causal diagonal.  They get a loop of their own so that the main loop has a
+    // single straight-line body.
+    const int it_masked_end = key0 + BK > N ? n_qtiles : (CAUSAL ? min(n_qtiles, (key0 + BK - 1) / BQ + 1) : it0);
+
+    auto iteration = [&](int it, auto mask_tag) {
         const int st = (it - it0) & 1;
         const int q0 = it * BQ;
         const bool more = it + 1 < n_qtiles;
         if (more) load_tile(it + 1);
 
-        i32x4 pa[2][2], dsa[2][2];  // [query sub-tile][16-query slab]: P^T and dS^T as A operands
-        const bool need_mask = key0 + BK > N || (CAUSAL && key0 + BK - 1 > q0);
-
-        // ---- S = Q_i K_j^T and dP = dO_i V_j^T for both 32-query sub-tiles.  With one wave per SIMD
-        // nothing else hides LDS latency, so operand reads run kPipe steps ahead of the MFMAs.
-        f32x16 sacc[2], pacc[2];
-        {
+        // One wave per SIMD: nothing but this wave's own instruction stream can keep the matrix
+        // pipe busy while the exponentials run.  The iteration is therefore software-pipelined by
+        // hand over its two 32-query sub-tiles (the intra-warpgroup overlap of the paper's
+        // Algorithm 2, applied to the backward pass):
+        //   stage 1: S, dP of sub-tile 0                      (MFMA only)
+        //   stage 2: S, dP of sub-tile 1  ||  P, dS of sub-tile 0
+        //   stage 3: dV, dK += sub-tile 0 ||  P, dS of sub-tile 1
+        //   stage 4: dV, dK += sub-tile 1                     (MFMA only)
+        // Every step ends in a full scheduling barrier so the interleaving below is what runs, and
+        // LDS operand reads lead their MFMAs by kPipe steps.
+        auto body = [&](auto mask_tag) {
+            constexpr bool MASK = decltype(mask_tag)::value;
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            constexpr int NU = 2 * KS;
-            const uint16_t* qrow = lds_q[st] + col * RSTR + half * 8;
-            const uint16_t* dorow = lds_do[st] + col * RSTR + half * 8;
-            i32x4 aq[kPipe], ado[kPipe];
-#pragma unroll
-            for (int u = 0; u < kPipe; ++u) {
-                aq[u] = *reinterpret_cast<const i32x4*>(qrow + (u / KS) * 32 * RSTR + (u % KS) * 16);
-                ado[u] = *reinterpret_cast<const i32x4*>(dorow + (u / KS) * 32 * RSTR + (u % KS) * 16);
-            }
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int sub = u / KS, ks = u % KS;
-                i32x4 a0 = aq[u % kPipe], a1 = ado[u % kPipe];
-                if (u + kPipe < NU) {
-                    const int v = u + kPipe;
-                    aq[u % kPipe] = *reinterpret_cast<const i32x4*>(qrow + (v / KS) * 32 * RSTR + (v % KS) * 16);
-                    ado[u % kPipe] = *reinterpret_cast<const i32x4*>(dorow + (v / KS) * 32 * RSTR + (v % KS) * 16);
-                }
-                sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
-                pacc[sub] = E::mma(a1, vreg[ks], ks == 0 ? zero : pacc[sub]);
-                __builtin_amdgcn_sched_barrier(0x6);  // only VALU / SALU may move across a step
-            }
-        }
+            i32x4 pa[2][2], dsa[2][2];  // [sub-tile][16-query slab]: P^T and dS^T as A operands
+            f32x16 sacc[2], pacc[2];
 
-        // ---- P = exp(S - L), dS = P o (dP - D); pack as A operands
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-            float pv[16], dsv[16];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
+            // L (log2 units) and D of the lane's query rows, fetched four rows at a time one step
+            // before they are needed so that few of them are live at once
+            f32x4 l4[2][4], d4[2][4];
+            auto fetch_ld = [&](int sub, int g) {
                 const int ql = sub * 32 + 8 * g + 4 * half;  // first of 4 consecutive query rows
-                f32x4 l4 = *reinterpret_cast<const f32x4*>(&lds_l[st][ql]);
-                f32x4 d4 = *reinterpret_cast<const f32x4*>(&lds_d[st][ql]);
+                l4[sub][g] = *reinterpret_cast<const f32x4*>(&lds_l[st][ql]);
+                d4[sub][g] = *reinterpret_cast<const f32x4*>(&lds_d[st][ql]);
+            };
+
+            // elements 2c, 2c+1 of a sub-tile: P, dS and one packed register of each
+            auto softmax_pair = [&](int sub, int c) {
+                float pv[2], dsv[2];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    float p = fast_exp2(__builtin_fmaf(sacc[sub][4 * g + r], sc, -l4[r]));
-                    if (need_mask) {
-                        bool masked = my_key >= N || (CAUSAL && my_key > q0 + ql + r);
+                for (int e = 0; e < 2; ++e) {
+                    const int rr = 2 * c + e, g = rr >> 2, r = rr & 3;
+                    float p = fast_exp2(__builtin_fmaf(sacc[sub][rr], sc, -l4[sub][g][r]));
+                    if constexpr (MASK) {
+                        const int qi = q0 + sub * 32 + 8 * g + 4 * half + r;
+                        const bool masked = my_key >= N || (CAUSAL && my_key > qi);
                         p = masked ? 0.f : p;
                     }
-                    pv[4 * g + r] = p;
-                    dsv[4 * g + r] = p * (pacc[sub][4 * g + r] - d4[r]);
+                    pv[e] = p;
+                    dsv[e] = p * (pacc[sub][rr] - d4[sub][g][r]);
                 }
-            }
-#pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    pa[sub][s2][e] = E::pack2(pv[8 * s2 + 2 * e], pv[8 * s2 + 2 * e + 1]);
-                    dsa[sub][s2][e] = E::pack2(dsv[8 * s2 + 2 * e], dsv[8 * s2 + 2 * e + 1]);
-                }
-            }
-        }
+                pa[sub][c >> 2][c & 3] = E::pack2(pv[0], pv[1]);
+                dsa[sub][c >> 2][c & 3] = E::pack2(dsv[0], dsv[1]);
+            };
 
-        // ---- dV_j += P^T dO_i,  dK_j += dS^T Q_i   (contract over the tile's queries)
-        {
-            constexpr int NU = 2 * 2 * DT;  // (sub, slab, d-tile)
-            const int rbase = (4 * half + tr_row) * RSTR + tr_col;
-            auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + (u % DT) * 32; };
-            i32x2 dlo[kPipe], dhi[kPipe], qlo[kPipe], qhi[kPipe];
+            // ---- stages 1 and 2: S = Q_i K_j^T, dP = dO_i V_j^T
+            {
+                constexpr int NU = 2 * KS;
+                const uint16_t* qrow = lds_q[st] + col * RSTR + half * 8;
+                const uint16_t* dorow = lds_do[st] + col * RSTR + half * 8;
+                i32x4 aq[kPipe], ado[kPipe];
 #pragma unroll
-            for (int u = 0; u < kPipe; ++u) {
-                dlo[u] = lds_read_tr16(lds_do[st] + off(u));
-                dhi[u] = lds_read_tr16(lds_do[st] + off(u) + 8 * RSTR);
-                qlo[u] = lds_read_tr16(lds_q[st] + off(u));
-                qhi[u] = lds_read_tr16(lds_q[st] + off(u) + 8 * RSTR);
-            }
-#pragma unroll
-            for (int u = 0; u < NU; ++u) {
-                const int sub = u / (2 * DT), s2 = (u / DT) % 2, dt = u % DT;
-                const int w = u % kPipe;
-                i32x4 b = {dlo[w][0], dlo[w][1], dhi[w][0], dhi[w][1]};
-                i32x4 b2 = {qlo[w][0], qlo[w][1], qhi[w][0], qhi[w][1]};
-                if (u + kPipe < NU) {
-                    dlo[w] = lds_read_tr16(lds_do[st] + off(u + kPipe));
-                    dhi[w] = lds_read_tr16(lds_do[st] + off(u + kPipe) + 8 * RSTR);
-                    qlo[w] = lds_read_tr16(lds_q[st] + off(u + kPipe));
-                    qhi[w] = lds_read_tr16(lds_q[st] + off(u + kPipe) + 8 * RSTR);
+                for (int u = 0; u < kPipe; ++u) {
+                    aq[u] = *reinterpret_cast<const i32x4*>(qrow + (u / KS) * 32 * RSTR + (u % KS) * 16);
+                    ado[u] = *reinterpret_cast<const i32x4*>(dorow + (u / KS) * 32 * RSTR + (u % KS) * 16);
                 }
-                dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
-                dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
-                __builtin_amdgcn_sched_barrier(0x6);
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    const int sub = u / KS, ks = u % KS;
+                    i32x4 a0 = aq[u % kPipe], a1 = ado[u % kPipe];
+                    if (u + kPipe < NU) {
+                        const int v = u + kPipe;
+                        aq[u % kPipe] = *reinterpret_cast<const i32x4*>(qrow + (v / KS) * 32 * RSTR + (v % KS) * 16);
+                        ado[u % kPipe] = *reinterpret_cast<const i32x4*>(dorow + (v / KS) * 32 * RSTR + (v % KS) * 16);
+                    }
+                    sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
+                    pacc[sub] = E::mma(a1, vreg[ks], ks == 0 ? zero : pacc[sub]);
+                    if (sub == 0 && ks == KS - 1) fetch_ld(0, 0);
+                    if (sub == 1) {
+                        if (ks % 2 == 1 && ks / 2 + 1 < 4) fetch_ld(0, ks / 2 + 1);
+                        if (ks == KS - 1) fetch_ld(1, 0);
+                        softmax_pair(0, ks);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
-        }
+
+            // ---- stages 3 and 4: dV_j += P^T dO_i, dK_j += dS^T Q_i (contract over the tile's queries)
+            {
+                constexpr int NU = 2 * 2 * DT;  // (sub, slab, d-tile)
+                const int rbase = (4 * half + tr_row) * RSTR + tr_col;
+                auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + (u % DT) * 32; };
+                i32x2 dlo[kPipe], dhi[kPipe], qlo[kPipe], qhi[kPipe];
+#pragma unroll
+                for (int u = 0; u < kPipe; ++u) {
+                    dlo[u] = lds_read_tr16(lds_do[st] + off(u));
+                    dhi[u] = lds_read_tr16(lds_do[st] + off(u) + 8 * RSTR);
+                    qlo[u] = lds_read_tr16(lds_q[st] + off(u));
+                    qhi[u] = lds_read_tr16(lds_q[st] + off(u) + 8 * RSTR);
+                }
+#pragma unroll
+                for (int u = 0; u < NU; ++u) {
+                    const int sub = u / (2 * DT), s2 = (u / DT) % 2, dt = u % DT;
+                    const int w = u % kPipe;
+                    i32x4 b = {dlo[w][0], dlo[w][1], dhi[w][0], dhi[w][1]};
+                    i32x4 b2 = {qlo[w][0], qlo[w][1], qhi[w][0], qhi[w][1]};
+                    if (u + kPipe < NU) {
+                        dlo[w] = lds_read_tr16(lds_do[st] + off(u + kPipe));
+                        dhi[w] = lds_read_tr16(lds_do[st] + off(u + kPipe) + 8 * RSTR);
+                        qlo[w] = lds_read_tr16(lds_q[st] + off(u + kPipe));
+                        qhi[w] = lds_read_tr16(lds_q[st] + off(u + kPipe) + 8 * RSTR);
+                    }
+                    dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
+                    dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
+                    if (sub == 0) {
+                        if (u % 2 == 1 && u / 2 + 1 < 4) fetch_ld(1, u / 2 + 1);
+                        softmax_pair(1, u);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        };
+        body(mask_tag);
 
         if (more) store_tile(st ^ 1);
         __syncthreads();
-    }
+    };
+    int it = it0;
+    for (; it < it_masked_end; ++it) iteration(it, std::true_type{});
+    for (; it < n_qtiles; ++it) iteration(it, std::false_type{});
 
     // ---- epilogue: dK_j = scale * acc, dV_j = acc  (rows = keys 8g+4h+r of this wave, col = d)
 #pragma unroll
@@ -284,7 +324,8 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     constexpr int D = kBwdD;
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
-    constexpr int RSTR = D + 8;
+    constexpr int RSTR = D + 24;  // K tile: row reads and transposed reads (304 B)
+    constexpr int VSTR = D + 8;   // V tile: row reads only (272 B)
     constexpr int KT = BC / 32;
     constexpr int KS = D / 16;
     constexpr int DT = D / 32;
@@ -295,7 +336,7 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     using E = Elem<Tag>;
 
     __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][BC * RSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][BC * RSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][BC * VSTR];
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -348,7 +389,7 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             int c = tid + i * NT;
             int row = c / CPR, cc = c % CPR;
             *reinterpret_cast<i32x4*>(lds_k[st] + row * RSTR + cc * 8) = kpre[i];
-            *reinterpret_cast<i32x4*>(lds_v[st] + row * RSTR + cc * 8) = vpre[i];
+            *reinterpret_cast<i32x4*>(lds_v[st] + row * VSTR + cc * 8) = vpre[i];
         }
     };
     load_tile(0);
@@ -371,13 +412,13 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
             // ---- S^T = K_j Q_i^T and dP^T = V_j dO_i^T
             f32x16 sacc[KT], pacc[KT];
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            const int rbase = col * RSTR + half * 8;
+            const int kbase = col * RSTR + half * 8, vbase = col * VSTR + half * 8;
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt) {
-                    i32x4 ak = *reinterpret_cast<const i32x4*>(lds_k[st] + rbase + kt * 32 * RSTR + ks * 16);
-                    i32x4 av = *reinterpret_cast<const i32x4*>(lds_v[st] + rbase + kt * 32 * RSTR + ks * 16);
+                    i32x4 ak = *reinterpret_cast<const i32x4*>(lds_k[st] + kbase + kt * 32 * RSTR + ks * 16);
+                    i32x4 av = *reinterpret_cast<const i32x4*>(lds_v[st] + vbase + kt * 32 * VSTR + ks * 16);
                     sacc[kt] = E::mma(ak, qreg[ks], ks == 0 ? zero : sacc[kt]);
                     pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? zero : pacc[kt]);
                 }
