@@ -21,6 +21,12 @@ SEQLENS = (512, 1024, 2048, 4096, 8192, 16384)
 HEAD_DIM = 128
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 PEAK_FP8_TFLOPS = 5000.0
+# HBM bytes per launch of the dominant kernel (the 8-wave non-causal d=128 kernel, which serves
+# seqlen 1k..16k: average over those five shapes), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/fa_fwd_bf16_d128_hbm_traffic.txt (copy-kernel calibration factors 2.000
+# and 1.000): four shapes move 257 MiB, seqlen 16k moves 385 MiB.  Algorithmic: 2.695e8 bytes.
+TRAFFIC_BYTES_PER_LAUNCH = 2.963e8
+DOMINANT_MIN_SEQLEN = 1024  # the launcher uses the 4-wave tile below this (non-causal)
 
 
 def _cpu_baseline():
@@ -47,6 +53,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extra", action="store_true", help="skip the untimed per-config table")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="for rocprofv3 --pmc runs: a plain 256 MiB device copy (calibration) followed by the "
+                         "six non-causal forward launches, three times each; prints nothing")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
@@ -84,6 +93,16 @@ def main():
                     e1.record(stream)
                     events.append((N, causal, e0, e1))
 
+    if args.traffic_probe:
+        src = torch.empty(256 << 20, device=dev, dtype=torch.uint8).random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+            for (N, B, H, q, k, v, o, lse) in work:
+                binding.fa_fwd(q, k, v, scale, False, o=o, lse=lse)
+        torch.cuda.synchronize()
+        return
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -98,20 +117,21 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     value = step_flops / (elapsed / args.steps) / 1e12
 
-    # dominant kernel: the non-causal d=128 bf16 forward (about two thirds of the step's time)
-    dur_ms, flops_nc, per_point = 0.0, 0.0, {}
+    # dominant kernel: fa_fwd_16bit_kernel<bf16, D=128, BC=128, NW=8, causal=false> (non-causal, seqlen >= 1k;
+    # about 60 % of the step's time); its duration comes from HIP events on the launch stream
+    dur_ms, flops_dom, n_launch, per_point = 0.0, 0.0, 0, {}
     for (N, causal, e0, e1) in events:
         ms = e0.elapsed_time(e1)
         per_point.setdefault((N, causal), []).append(ms)
-        if not causal:
+        if not causal and N >= DOMINANT_MIN_SEQLEN:
             dur_ms += ms
+            n_launch += 1
             B, H = inputs.benchmark_shape(N, d)
-            flops_nc += binding.attention_flops(B, H, N, d, False)
-    n_launch = args.steps * len(SEQLENS)
-    achieved = flops_nc / (dur_ms * 1e-3) / 1e12
+            flops_dom += binding.attention_flops(B, H, N, d, False)
+    achieved = flops_dom / (dur_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
-                "kernel": "fa_fwd_16bit_kernel<bf16, d=128, causal=false>",
+                "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
+                "kernel": "fa_fwd_16bit_kernel<bf16_tag, 128, 128, 8, 1, 0, false>",
                 "avg_launch_ms": round(dur_ms / n_launch, 4), "launches": n_launch}
 
     points = {}
