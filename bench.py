@@ -21,7 +21,7 @@ SEQLENS = (512, 1024, 2048, 4096, 8192, 16384)
 HEAD_DIM = 128
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 PEAK_FP8_TFLOPS = 5000.0
-# HBM bytes per launch of the dominant kernel (the 8-wave non-causal d=128 kernel, which serves
+# HBM bytes per launch of the dominant kernel (the ping-pong non-causal d=128 kernel, which serves
 # seqlen 1k..16k: average over those five shapes), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/fa_fwd_bf16_d128_hbm_traffic.txt (copy-kernel calibration factors 2.000
 # and 1.000): four shapes move 257 MiB, seqlen 16k moves 385 MiB.  Algorithmic: 2.695e8 bytes.
@@ -117,7 +117,7 @@ def main():
     ms_per_step = elapsed / args.steps * 1e3
     value = step_flops / (elapsed / args.steps) / 1e12
 
-    # dominant kernel: fa_fwd_16bit_kernel<bf16, D=128, BC=128, NW=8, causal=false> (non-causal, seqlen >= 1k;
+    # dominant kernel: fa_fwd_pingpong_kernel<bf16, BC=64, P=4, causal=false> (non-causal, seqlen >= 1k;
     # about 60 % of the step's time); its duration comes from HIP events on the launch stream
     dur_ms, flops_dom, n_launch, per_point = 0.0, 0.0, 0, {}
     for (N, causal, e0, e1) in events:
@@ -131,7 +131,7 @@ def main():
     achieved = flops_dom / (dur_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "achieved": round(achieved, 1), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": TRAFFIC_BYTES_PER_LAUNCH,
-                "kernel": "fa_fwd_16bit_kernel<bf16_tag, 128, 128, 8, 1, 0, false>",
+                "kernel": "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>",
                 "avg_launch_ms": round(dur_ms / n_launch, 4), "launches": n_launch}
 
     points = {}

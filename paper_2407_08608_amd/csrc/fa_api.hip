@@ -16,6 +16,9 @@ int check_common(int B, int H, int N, int d, float scale, int causal) {
     if (causal != 0 && causal != 1) return FA_ERR_SHAPE;
     if ((long)B * H * N > 0x7fffffffL) return FA_ERR_SHAPE;
     if (!head_dim_ok(d)) return FA_ERR_UNSUPPORTED;
+    // one head of a tensor is addressed through a 32-bit buffer offset (4 bytes per element at most,
+    // and the staging loads run a few blocks past the end)
+    if ((long)N * d * 4 > 0x7ff00000L) return FA_ERR_UNSUPPORTED;
     return FA_OK;
 }
 

@@ -116,6 +116,27 @@ static __device__ __forceinline__ i32x4 buffer_load_16B(__amdgpu_buffer_rsrc_t r
     return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(rsrc, byte_off, 0, 0));
 }
 
+// Asynchronous global -> LDS copy of 16 bytes per lane (buffer load with an LDS destination):
+// lane i's bytes land at lds_base + 16 i, lds_base wave-uniform; reads past the resource's size
+// store zeros.  Written as inline assembly on purpose: the compiler then does not know that the
+// load writes LDS and does not drain all outstanding loads before every later LDS read; the
+// caller orders the two with an explicit vmcnt wait and a barrier.
+struct BufferWords {
+    i32x4 w;
+};
+static __device__ __forceinline__ BufferWords make_buffer_words(const void* base, uint32_t bytes) {
+    const uint64_t a = reinterpret_cast<uint64_t>(base);
+    BufferWords b;
+    b.w = i32x4{(int)(uint32_t)a, (int)(uint32_t)((a >> 32) & 0xFFFF), (int)bytes, 0x00020000};
+    return b;
+}
+static __device__ __forceinline__ void global_to_lds_16B(const BufferWords& rsrc, uint32_t lds_base, int byte_off) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(byte_off), "s"(rsrc.w)
+                 : "memory", "m0");
+}
+
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // The chip deals consecutive workgroup ids round-robin to its 8 XCDs, each with a private

@@ -7,6 +7,8 @@
 // exp(m_old - m_new); epilogue O / l and L = m + log l.  K_j and V_j are staged through a
 // double-buffered LDS ring that the next block's global loads fill while the current block
 // is being computed (the role the producer warpgroup plays in the paper).
+#include <type_traits>
+
 #include "fa_device.h"
 #include "fa_launch.h"
 
@@ -305,6 +307,323 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------
+// Eight-wave ping-pong variant (head dimension 128).
+//
+// An eight-wave workgroup puts two waves on every SIMD (waves w and w + 4).  If all of them run
+// a block's steps in the same order they stay in lock-step: both waves of a SIMD issue MFMAs
+// together and then both do softmax together, so the matrix pipe idles during every softmax --
+// the problem the paper's ping-pong scheduling (section 3.1) solves with named barriers between
+// two warpgroups.  Here the waves form two groups, one wave of each per SIMD, and every
+// iteration has two half-steps separated by workgroup barriers:
+//
+//     iteration t          half-step 1                   half-step 2
+//        group A     MFMA stream(t)                 softmax(t), operand prefetch
+//        group B     softmax(t-1), prefetch         MFMA stream(t)
+//
+//     stream(t) = O^T += V(t-1)^T P~(t-1)^T  followed by  S(t)^T = K(t) Q^T
+//
+// so that one wave of each SIMD always has MFMA work while the other has VALU work.  Group A
+// carries P~ from one iteration to the next, group B carries S.  A stream is one sequence of
+// (LDS operand read, MFMA) units whose reads run P units ahead of their use through a register
+// ring; the first P reads are issued before the barrier that precedes the stream, so they
+// complete while the wave waits there.
+//
+// Staging: K and V blocks go from global memory straight into a ring of NS LDS stages
+// (buffer loads with an LDS destination: no staging registers, no LDS store instructions), issued
+// two to three iterations before their first use.  Such a load writes 64 lanes x 16 bytes
+// contiguously, so the tiles are stored unpadded (256 bytes per row) and bank conflicts are
+// avoided by an XOR swizzle of the 16-byte chunk index instead, applied through the *global*
+// address each lane fetches:  K: chunk ^ (row % 16)  (16 lanes read 16 rows at one chunk),
+// V: chunk ^ 4 (row % 4)  (a transposing read covers 4 rows x 4 chunks).
+template <typename Tag, int BC, int P, bool CAUSAL>
+__global__ void __launch_bounds__(512, 2)
+fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+                       const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
+                       int N, int n_qtiles, int total_wg, float scale) {
+    constexpr int D = 128;
+    constexpr int BR = 256;
+    constexpr int NS = 4;              // LDS stages per tensor
+    constexpr int ROWB = D * 2;        // bytes per tile row
+    constexpr int TILE = BC * ROWB;    // bytes per stage
+    constexpr int KT = BC / 32;
+    constexpr int KS = D / 16;
+    constexpr int DT = D / 32;
+    constexpr int SL = BC / 16;
+    constexpr int N1 = SL * DT;  // MFMA units of the second GEMM
+    constexpr int N0 = KS * KT;  // MFMA units of the first GEMM
+    static_assert(BC == 64, "the staging pattern below covers 64-row tiles with two loads per wave");
+    using E = Elem<Tag>;
+
+    __shared__ __attribute__((aligned(1024))) char lds_k[NS * TILE];
+    __shared__ __attribute__((aligned(1024))) char lds_v[NS * TILE];
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+    // the two waves of a SIMD take adjacent 32-row slabs of the query tile
+    const int group = wave >> 2;
+    const int slab = (wave & 3) * 2 + group;
+
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int bh = id / n_qtiles;
+    int qt = id % n_qtiles;
+    if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint16_t* qh = q + head_off;
+    const int wave_q0 = qt * BR + slab * 32;
+    const float sc = scale * kLog2e;
+    float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
+    asm volatile("" : "+v"(sc_v));
+
+    i32x4 qreg[KS];
+    {
+        int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qreg[ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
+    }
+
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int last_q = min(qt * BR + BR, N) - 1;
+    const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+    // blocks 0 .. nb_w-1 concern this wave (all of them unless causal)
+    const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
+
+    // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
+    const BufferWords k_rsrc = make_buffer_words(k + head_off, (uint32_t)N * D * 2);
+    const BufferWords v_rsrc = make_buffer_words(v + head_off, (uint32_t)N * D * 2);
+    const int st_row = 4 * wave + (lane >> 4), st_pos = lane & 15;
+    const int k_src = st_row * ROWB + ((st_pos ^ (st_row & 15)) << 4);        // byte offset within a tile
+    const int v_src = st_row * ROWB + ((st_pos ^ ((st_row & 3) << 2)) << 4);
+    const uint32_t lds_k0 = (uint32_t)(uintptr_t)lds_k + wave * 1024, lds_v0 = (uint32_t)(uintptr_t)lds_v + wave * 1024;
+    // Block u of K and block u2 of V.  Blocks past the end lie outside the buffer resources and
+    // read as zeros, so every iteration issues the same four loads and the vmcnt waits below can
+    // count on that.
+    auto stage_k = [&](int u) __attribute__((always_inline)) {
+        const uint32_t kd = lds_k0 + (u & (NS - 1)) * TILE;
+        global_to_lds_16B(k_rsrc, kd, k_src + u * TILE);
+        global_to_lds_16B(k_rsrc, kd + 8 * 1024, k_src + u * TILE + 32 * ROWB);
+    };
+    auto stage_v = [&](int u) __attribute__((always_inline)) {
+        const uint32_t vd = lds_v0 + (u & (NS - 1)) * TILE;
+        global_to_lds_16B(v_rsrc, vd, v_src + u * TILE);
+        global_to_lds_16B(v_rsrc, vd + 8 * 1024, v_src + u * TILE + 32 * ROWB);
+    };
+    auto stage = [&](int u, int u2) __attribute__((always_inline)) {
+        stage_k(u);
+        stage_v(u2);
+    };
+
+    // ---- per-lane operand offsets within a stage (bytes)
+    const int tr_row = (lane & 15) >> 2, quad = lane & 3, blk = (lane >> 4) & 1;
+    int kofs[KS], vofs[DT];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kofs[ks] = col * ROWB + (((2 * ks + half) ^ (col & 15)) << 4);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+        vofs[dt] = (4 * half + tr_row) * ROWB + (((4 * dt + 2 * blk + (quad >> 1)) ^ (tr_row << 2)) << 4) + 8 * (quad & 1);
+
+    f32x16 sacc[KT];
+    i32x4 pb[SL];
+    i32x4 ring[P];
+
+    // Unit u of stream(t): the second GEMM's units (if DO1) then the first GEMM's (if DO0).
+    auto read_unit = [&](auto do1, int t, int u) __attribute__((always_inline)) {
+        constexpr int n1 = decltype(do1)::value ? N1 : 0;
+        if (u < n1) {
+            const int sl = u / DT, dt = u % DT;
+            const char* p0 = lds_v + ((t - 1) & (NS - 1)) * TILE + vofs[dt] + sl * 16 * ROWB;
+            i32x2 lo = lds_read_tr16(p0);
+            i32x2 hi = lds_read_tr16(p0 + 8 * ROWB);
+            ring[u % P] = i32x4{lo[0], lo[1], hi[0], hi[1]};
+        } else {
+            const int ks = (u - n1) / KT, kt = (u - n1) % KT;
+            ring[u % P] = *reinterpret_cast<const i32x4*>(lds_k + (t & (NS - 1)) * TILE + kofs[ks] + kt * 32 * ROWB);
+        }
+    };
+    auto prefill = [&](auto do1, auto do0, int t) __attribute__((always_inline)) {
+        constexpr int NU = (decltype(do1)::value ? N1 : 0) + (decltype(do0)::value ? N0 : 0);
+#pragma unroll
+        for (int u = 0; u < (P < NU ? P : NU); ++u) read_unit(do1, t, u);
+    };
+    auto run_stream = [&](auto do1, auto do0, int t) __attribute__((always_inline)) {
+        constexpr int n1 = decltype(do1)::value ? N1 : 0;
+        constexpr int NU = n1 + (decltype(do0)::value ? N0 : 0);
+        const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int u = 0; u < NU; ++u) {
+            const i32x4 a = ring[u % P];
+            if (u + P < NU) read_unit(do1, t, u + P);
+            if (u < n1) {
+                const int sl = u / DT, dt = u % DT;
+                oacc[dt] = E::mma(a, pb[sl], oacc[dt]);
+            } else {
+                const int ks = (u - n1) / KT, kt = (u - n1) % KT;
+                sacc[kt] = E::mma(a, qreg[ks], ks == 0 ? zero : sacc[kt]);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    // mask block t (keys past N; keys after the query when causal), then the online softmax of
+    // Algorithm 1 (m, P~, l); P~ leaves packed as the B operand of the second GEMM
+    auto softmax = [&](int t) __attribute__((always_inline)) {
+        const int key0 = t * BC;
+        if ((key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0)) {
+            const int qi = wave_q0 + col;
+            const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (key > limit) sacc[kt][r] = -INFINITY;
+                }
+        }
+        // Every step below is a batch of independent instructions: a wave gets few issue slots
+        // while its SIMD sibling streams MFMAs, and dependent chains (max, fma -> exp, sum)
+        // would turn each slot missed into a stall.
+        float mxp[4];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mxp[c] = sacc[0][c];
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
+        float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])));
+        // lazily raised reference maximum, as in fa_fwd_16bit_kernel
+        const bool raise = (mx - m_run) * sc > kLazyLog2;
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            float corr = raise ? fast_exp2((m_run - mx) * sc) : 1.0f;
+            m_run = raise ? mx : m_run;
+            l_run *= corr;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) oacc[dt][r] *= corr;
+        }
+        const float mb = m_run * sc;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[kt][r] = __builtin_fmaf(sacc[kt][r], sc_v, -mb);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sacc[kt][r] = fast_exp2(sacc[kt][r]);
+        __builtin_amdgcn_sched_barrier(0);
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kt = 0; kt < KT; ++kt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) ps[r & 3] += sacc[kt][r];
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                i32x4 w;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) w[e] = E::pack2(sacc[kt][8 * s2 + 2 * e], sacc[kt][8 * s2 + 2 * e + 1]);
+                pb[2 * kt + s2] = w;
+            }
+        }
+        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        // P~ must exist in registers here: the compiler is otherwise free to sink the exponentials
+        // past the next barrier, next to the MFMAs that consume them
+#pragma unroll
+        for (int i = 0; i < SL; ++i) asm volatile("" : "+v"(pb[i]));
+    };
+
+    // Workgroup barrier that leaves the staging loads in flight.  LDS reads issued before it (the
+    // operand prefetch) may still be outstanding; their results are only used after it anyway.
+    auto barrier = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    // Iteration t issues K(t+3) and V(t+2) (four loads per wave); before the barrier that ends
+    // half-step 1 of iteration t a wave makes sure its loads of iteration t-2 have landed: K(t+1)
+    // and V(t), first read by the prefetch at the end of this iteration.
+    auto mid_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        barrier();
+    };
+
+    const std::true_type yes{};
+    const std::false_type no{};
+
+    // ---- prologue: K(0), K(1), K(2), V(0), V(1) staged and visible before the first iteration
+    stage(0, 0);
+    stage(1, 1);
+    stage_k(2);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));  // Q loads complete before the loop
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    barrier();
+
+    if (group == 0) {
+        prefill(no, yes, 0);
+        // stream(t) was prefetched at the end of the previous iteration
+        auto iteration = [&](int t, auto do1, auto do0, auto next1, auto next0) __attribute__((always_inline)) {
+            stage(t + 3, t + 2);
+            run_stream(do1, do0, t);
+            mid_barrier();
+            if constexpr (decltype(do0)::value) softmax(t);
+            prefill(next1, next0, t + 1);
+            barrier();
+        };
+        // stream shapes over t: (no,yes) at 0; (yes,yes) for 1..nb_w-1; (yes,no) at nb_w; nothing after
+        if (nb_w > 1) iteration(0, no, yes, yes, yes);
+        else iteration(0, no, yes, yes, no);
+        for (int t = 1; t + 1 < nb_w; ++t) iteration(t, yes, yes, yes, yes);
+        if (nb_w > 1) iteration(nb_w - 1, yes, yes, yes, no);
+        iteration(nb_w, yes, no, no, no);
+        for (int t = nb_w + 1; t <= n_blocks; ++t) iteration(t, no, no, no, no);
+    } else {
+        auto iteration = [&](int t, auto do1, auto do0) __attribute__((always_inline)) {
+            stage(t + 3, t + 2);
+            prefill(do1, do0, t);
+            if constexpr (decltype(do1)::value) softmax(t - 1);
+            mid_barrier();
+            run_stream(do1, do0, t);
+            barrier();
+        };
+        iteration(0, no, yes);
+        for (int t = 1; t < nb_w; ++t) iteration(t, yes, yes);
+        iteration(nb_w, yes, no);
+        for (int t = nb_w + 1; t <= n_blocks; ++t) iteration(t, no, no);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // staging loads past the last block: nothing may land after the end
+
+    // ---- epilogue: O / l, L = m + log l
+    const int qi = wave_q0 + col;
+    const float l = sum_both_halves(l_run);
+    const float inv = 1.0f / l;
+    if (qi < N) {
+        uint16_t* orow = o + head_off + (size_t)qi * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                i32x2 w;
+                w[0] = E::pack2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
+                w[1] = E::pack2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
+                *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
+            }
+        if (half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------
 // fp32 path (d = 64): plain fp32 FMA arithmetic with the same structure -- a query tile per
 // workgroup, K/V blocks staged in LDS, online softmax with exp2 and the scale folded in.
 // One thread owns one query row, so no cross-lane reductions are needed.
@@ -396,10 +715,33 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
-// Tile choice (measured on MI355X at the 16k-token benchmark shapes):
-//   d = 64, 128: eight waves share each K/V block (256 query rows per workgroup, two waves per
-//     SIMD), which halves the L2->LDS traffic per FLOP; short causal problems keep 128-row
-//     workgroups so that fewer waves idle on the diagonal.
+template <typename Tag>
+static int launch_pingpong(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+                           float scale, int causal, hipStream_t stream) {
+    constexpr int BR = 256, BC = 64, P = 4;
+    int n_qtiles = (N + BR - 1) / BR;
+    long total = (long)B * H * n_qtiles;
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(512);
+    auto qp = static_cast<const uint16_t*>(q);
+    auto kp = static_cast<const uint16_t*>(k);
+    auto vp = static_cast<const uint16_t*>(v);
+    auto op = static_cast<uint16_t*>(o);
+    if (causal)
+        hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
+                           n_qtiles, (int)total, scale);
+    else
+        hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
+                           n_qtiles, (int)total, scale);
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
+// Kernel choice (measured on MI355X at the 16k-token benchmark shapes):
+//   d = 128: the eight-wave ping-pong kernel from 1024 keys on (causal: from 4096 on); shorter
+//     problems keep 128-row workgroups of four waves, which fill the chip better and leave fewer
+//     waves idle on the causal diagonal.
+//   d = 64: eight waves share each K/V block (256 query rows per workgroup, two waves per SIMD),
+//     four waves for short problems.
 //   d = 256: the 128-register output accumulator allows only one wave per SIMD, so the operand
 //     reads are software-pipelined eight MFMA steps ahead instead.
 template <typename Tag>
@@ -412,7 +754,7 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
             return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
         case 128:
             if (small_tile) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            return launch_16bit<Tag, 128, 128, 8, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            return launch_pingpong<Tag>(q, k, v, o, lse, B, H, N, scale, causal, stream);
         case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
