@@ -63,6 +63,18 @@ def test_bf16_every_block_visited_once(N, causal):
     _check_full(q, k, v, 128 ** -0.5, causal)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("N,causal", [(1024, False), (1031, False), (1100, False), (1345, False), (2049, False),
+                                      (4096, True), (4129, True), (4200, True)])
+def test_16bit_d128_pingpong_kernel_ragged(N, causal, dtype):
+    # head dimension 128 from 1024 keys on (causal: above 2048) runs the eight-wave ping-pong kernel
+    # with its own staging ring and 256-row query tiles: whole and ragged tiles, ragged key blocks,
+    # a single query tile with all four staged blocks in use, and the causal diagonal
+    B, H = (1, 2) if causal else (2, 2)
+    q, k, v = inputs.qkv(70 + N, B, H, N, 128, dtype)
+    _check_full(q, k, v, 128 ** -0.5, causal)
+
+
 def test_bf16_constant_value_rows_and_causal_row_zero():
     B, H, N, d = 1, 2, 320, 128
     q, k, v = inputs.qkv(5, B, H, N, d, "bf16")
