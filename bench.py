@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a plain 256 MiB device copy (calibration) followed by the "
                          "six non-causal forward launches, three times each; prints nothing")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="instead of the benchmark: the MFMA-only rate of the chip (bf16 and e4m3) on constant and "
+                         "on random operand bits; prints one JSON line")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU; run with --gpus 1 "
@@ -68,6 +71,9 @@ def main():
         sys.exit("bench.py: no GPU visible")
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.mfma_probe:
+        print(json.dumps(mfma_probe(torch, binding, inputs, dev)))
+        return
     d = HEAD_DIM
     scale = d ** -0.5
 
@@ -157,6 +163,31 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline()
     print(json.dumps(out))
+
+
+def mfma_probe(torch, binding, inputs, dev):
+    """MFMA-only rate: every wave of a full-chip launch issues independent MFMAs and nothing else.
+    `ones` = all operands 1.0; `attention_like` = the bits of N(0,1) draws in bf16, or of the e4m3
+    codes of N(0,1) scaled so that the largest magnitude maps to 448.  The drop from `ones` to
+    `attention_like` is the clock the chip gives up to the switching activity of real operands."""
+    import numpy as np
+    out = {"what": "MFMA-only rate, 512 workgroups x 8 waves, TFLOP/s", "peak_bf16": PEAK_BF16_TFLOPS,
+           "peak_fp8": PEAK_FP8_TFLOPS}
+    x = inputs.normal_tensor(7, "probe", (1 << 16,), "bf16")
+    amax = float(x.abs().max())
+    operands = {
+        ("bf16", "ones"): torch.ones(1 << 16, dtype=torch.bfloat16).view(torch.uint8),
+        ("bf16", "attention_like"): x.view(torch.uint8),
+        ("fp8", "ones"): torch.full((1 << 16,), 0x38, dtype=torch.uint8),
+        ("fp8", "attention_like"): (x.float() * (448.0 / amax)).to(torch.float8_e4m3fn).view(torch.uint8),
+    }
+    iters = 20000
+    for (name, kind), bits in operands.items():
+        code = binding.FA_BF16 if name == "bf16" else binding.FA_FP8_E4M3
+        t = bits.contiguous().to(dev)
+        ms = _time_call(torch, lambda: binding.fa_probe_mfma(t, code, iters), reps=8, warm=4)
+        out[f"{name}_{kind}"] = round(binding.fa_probe_mfma_flops(code, iters) / ms / 1e9, 1)
+    return out
 
 
 def _time_call(torch, fn, reps=10, warm=2):

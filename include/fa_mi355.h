@@ -119,6 +119,25 @@ int fa_bwd(const void* q, const void* k, const void* v, const void* o, const flo
            const void* dout, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
            int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
 
+/*
+ * Measurement aid, not part of the attention path: the rate of the matrix pipes alone.  The
+ * roofline fractions of the kernels above are quoted against the published MFMA peak; this
+ * call measures what the chip sustains when every wave issues only independent MFMAs
+ * (bf16 32x32x16 for FA_BF16, e4m3 32x32x64 for FA_FP8_E4M3) on operand bits of the caller's
+ * choosing, which is the practical ceiling for an MFMA-bound kernel on such data.
+ *   operands      : device, read; operand_bytes (a multiple of 16, at most 1 GiB) of raw
+ *                   operand bits in `dtype`; each lane loads 128 bytes from it once
+ *   sink          : device, at least 512 floats; never written in practice (it keeps the
+ *                   arithmetic observable)
+ *   iters         : 1 .. 1e6 loop trips of 32 MFMAs per wave
+ * One launch of 512 workgroups x 8 waves performs fa_probe_mfma_flops(dtype, iters) FLOPs
+ * (0.0 for an unsupported dtype or iters <= 0); the caller times it.
+ */
+double fa_probe_mfma_flops(int dtype, int iters);
+
+int fa_probe_mfma(const void* operands, size_t operand_bytes, float* sink, int dtype, int iters,
+                  void* stream);
+
 /* Static, NUL-terminated description of an fa_status value. */
 const char* fa_status_string(int status);
 

@@ -17,7 +17,7 @@ FA_F32, FA_BF16, FA_F16, FA_FP8_E4M3 = 0, 1, 2, 3
 _DTYPE_CODE = {torch.float32: FA_F32, torch.bfloat16: FA_BF16, torch.float16: FA_F16}
 
 EXPORTS = ("fa_fwd", "fa_fwd_fp8", "fa_fp8_quant_hadamard", "fa_bwd_workspace_bytes", "fa_bwd",
-           "fa_status_string")
+           "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
 
 _lib = None
 
@@ -47,6 +47,10 @@ def lib():
         L.fa_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.fa_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_bwd.restype = ci
+        L.fa_probe_mfma_flops.argtypes = [ci, ci]
+        L.fa_probe_mfma_flops.restype = ctypes.c_double
+        L.fa_probe_mfma.argtypes = [vp, ctypes.c_size_t, fp, ci, ci, vp]
+        L.fa_probe_mfma.restype = ci
         L.fa_status_string.argtypes = [ci]
         L.fa_status_string.restype = ctypes.c_char_p
         _lib = L
@@ -138,6 +142,22 @@ def fa_bwd(q, k, v, o, lse, dout, scale, causal, dq=None, dk=None, dv=None, work
     if st != FA_OK:
         raise FaError(st, "fa_bwd")
     return dq, dk, dv
+
+
+def fa_probe_mfma_flops(dtype, iters):
+    return float(lib().fa_probe_mfma_flops(int(dtype), int(iters)))
+
+
+def fa_probe_mfma(operands, dtype, iters, sink=None):
+    """One launch of the MFMA-only rate probe on the raw operand bits in `operands` (uint8)."""
+    _check_dev(operands, sink)
+    if sink is None:
+        sink = torch.empty((512,), device=operands.device, dtype=torch.float32)
+    st = lib().fa_probe_mfma(operands.data_ptr(), operands.numel() * operands.element_size(), sink.data_ptr(),
+                             int(dtype), int(iters), _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_probe_mfma")
+    return sink
 
 
 def attention_flops(B, H, N, d, causal, backward=False):

@@ -106,4 +106,20 @@ int fa_bwd(const void* q, const void* k, const void* v, const void* o, const flo
                           static_cast<hipStream_t>(stream));
 }
 
+double fa_probe_mfma_flops(int dtype, int iters) {
+    if ((dtype != FA_BF16 && dtype != FA_FP8_E4M3) || iters <= 0) return 0.0;
+    return fa::probe_mfma_flops(iters, dtype == FA_FP8_E4M3);
+}
+
+int fa_probe_mfma(const void* operands, size_t operand_bytes, float* sink, int dtype, int iters, void* stream) {
+    if (!operands || !sink) return FA_ERR_NULL;
+    if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
+    if (dtype != FA_BF16 && dtype != FA_FP8_E4M3) return FA_ERR_UNSUPPORTED;
+    if (operand_bytes < 16 || operand_bytes % 16 != 0 || operand_bytes > (size_t)1 << 30 || iters <= 0 || iters > 1000000)
+        return FA_ERR_SHAPE;
+    if (!aligned16(operands) || !aligned16(sink)) return FA_ERR_ALIGN;
+    return fa::launch_probe_mfma(operands, operand_bytes, sink, iters, dtype == FA_FP8_E4M3,
+                                 static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

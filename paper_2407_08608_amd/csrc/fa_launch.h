@@ -23,5 +23,7 @@ size_t bwd_workspace_bytes(int B, int H, int N, int d);
 int launch_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
                void* dq, void* dk, void* dv, void* workspace, int B, int H, int N, int d, float scale, int causal,
                int dtype, hipStream_t stream);
+int launch_probe_mfma(const void* operands, size_t operand_bytes, float* sink, int iters, bool fp8, hipStream_t stream);
+double probe_mfma_flops(int iters, bool fp8);
 
 }  // namespace fa

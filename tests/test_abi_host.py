@@ -66,6 +66,19 @@ def test_fp8_and_bwd_entry_points_validate():
     assert L.fa_bwd(*args) == 6
 
 
+def test_mfma_probe_validates_and_counts_flops():
+    L = binding.lib()
+    # 512 workgroups x 8 waves x iters x 32 MFMAs of 2*32*32*16 (bf16) or 2*32*32*64 (e4m3) FLOPs
+    assert L.fa_probe_mfma_flops(binding.FA_BF16, 10) == 512 * 8 * 10 * 32 * 2 * 32 * 32 * 16
+    assert L.fa_probe_mfma_flops(binding.FA_FP8_E4M3, 10) == 512 * 8 * 10 * 32 * 2 * 32 * 32 * 64
+    assert L.fa_probe_mfma_flops(binding.FA_F16, 10) == 0.0
+    assert L.fa_probe_mfma(None, 1024, 16, binding.FA_BF16, 10, None) == 1
+    assert L.fa_probe_mfma(16, 1024, 16, binding.FA_F16, 10, None) == 4
+    assert L.fa_probe_mfma(16, 1000, 16, binding.FA_BF16, 10, None) == 2
+    assert L.fa_probe_mfma(16, 1024, 16, binding.FA_BF16, 0, None) == 2
+    assert L.fa_probe_mfma(8, 1024, 16, binding.FA_BF16, 10, None) == 5
+
+
 def test_flop_accounting_matches_the_papers_ablation_table():
     import json
     g = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_values.json")))
