@@ -110,3 +110,31 @@ def attention_probs(q, k, v, alpha, causal):
     P = np.empty((N, N), dtype=np.float64)
     _load().oracle_attn_probs(_p(q), _p(k), _p(v), _p(P), N, d, float(alpha), int(bool(causal)))
     return P
+
+
+def _expand_kv_heads(x, H):
+    """[B,H_kv,N,d] -> [B,H,N,d]: query head h reads key/value head h // (H / H_kv)."""
+    H_kv = x.shape[1]
+    assert H % H_kv == 0, "the number of query heads must be a multiple of the key/value heads"
+    return np.repeat(x, H // H_kv, axis=1)
+
+
+def attention_fwd_gqa(q, k, v, alpha, causal):
+    """Multi-query / grouped-query attention (section 3.1, "Attention variants"): q is [B,H,N,d],
+    k and v are [B,H_kv,N,d] with H_kv dividing H; consecutive groups of H/H_kv query heads share
+    one key/value head.  By definition this is ordinary attention on K and V repeated per group."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    H = q.shape[1]
+    return attention_fwd(q, _expand_kv_heads(k, H), _expand_kv_heads(v, H), alpha, causal)
+
+
+def attention_bwd_gqa(q, k, v, dout, alpha, causal):
+    """Gradients of the grouped-query forward: the repeat of K and V fans each key/value head out to
+    H/H_kv query heads, so its gradient is the sum of the per-query-head gradients of that group."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, N, d = q.shape
+    H_kv = k.shape[1]
+    r = attention_bwd(q, _expand_kv_heads(k, H), _expand_kv_heads(v, H), dout, alpha, causal)
+    r["dk"] = r["dk"].reshape(B, H_kv, H // H_kv, N, d).sum(axis=2)
+    r["dv"] = r["dv"].reshape(B, H_kv, H // H_kv, N, d).sum(axis=2)
+    return r

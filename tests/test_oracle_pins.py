@@ -234,3 +234,67 @@ def test_backward_constant_values_have_zero_query_key_gradients():
     np.testing.assert_allclose(g["dk"], 0.0, atol=1e-13)
     # dV columns sum to the column sums of dO (P is row-stochastic)
     np.testing.assert_allclose(g["dv"].sum(axis=2), dout.sum(axis=2), rtol=1e-12)
+
+
+# ---- multi-query / grouped-query attention (section 3.1, "Attention variants") -------------------------
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("H,H_kv", [(4, 4), (4, 2), (6, 2), (3, 1)])
+def test_gqa_forward_matches_library_softmax_per_query_head(H, H_kv, causal):
+    B, N, d = 2, 9, 4
+    q = _rand(11, B, H, N, d)
+    k, v = _rand(12, B, H_kv, N, d), _rand(13, B, H_kv, N, d)
+    o, lse = oracle.attention_fwd_gqa(q, k, v, 0.41, causal)
+    for b in range(B):
+        for h in range(H):
+            g = h // (H // H_kv)  # written out here independently of the oracle's helper
+            o_ref, l_ref = _library_attention(q[b, h], k[b, g], v[b, g], 0.41, causal)
+            np.testing.assert_allclose(o[b, h], o_ref, rtol=1e-12, atol=1e-13)
+            np.testing.assert_allclose(lse[b, h], l_ref, rtol=1e-12, atol=1e-13)
+
+
+def test_gqa_head_mapping_is_blocked_not_interleaved():
+    # two key/value heads with constant, distinct value rows: query heads 0,1 must return the first, 2,3 the second
+    B, H, H_kv, N, d = 1, 4, 2, 5, 3
+    q, k = _rand(14, B, H, N, d), _rand(15, B, H_kv, N, d)
+    v = np.empty((B, H_kv, N, d))
+    v[:, 0], v[:, 1] = 1.0, -2.0
+    o, _ = oracle.attention_fwd_gqa(q, k, v, 1.0, False)
+    np.testing.assert_allclose(o[:, :2], 1.0, rtol=1e-14)
+    np.testing.assert_allclose(o[:, 2:], -2.0, rtol=1e-14)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_gqa_backward_matches_finite_differences_of_the_forward(causal):
+    B, H, H_kv, N, d = 1, 4, 2, 6, 3
+    alpha = 0.6
+    q, dout = _rand(16, B, H, N, d), _rand(19, B, H, N, d)
+    k, v = _rand(17, B, H_kv, N, d), _rand(18, B, H_kv, N, d)
+    r = oracle.attention_bwd_gqa(q, k, v, dout, alpha, causal)
+    assert r["dk"].shape == k.shape and r["dv"].shape == v.shape and r["dq"].shape == q.shape
+
+    def loss(q_, k_, v_):
+        o, _ = oracle.attention_fwd_gqa(q_, k_, v_, alpha, causal)
+        return float((o * dout).sum())
+
+    eps = 1e-6
+    for name, x, g in (("dq", q, r["dq"]), ("dk", k, r["dk"]), ("dv", v, r["dv"])):
+        rng = np.random.default_rng(20)
+        for _ in range(12):
+            idx = tuple(rng.integers(0, s) for s in x.shape)
+            xp, xm = x.copy(), x.copy()
+            xp[idx] += eps
+            xm[idx] -= eps
+            args_p = {"dq": (xp, k, v), "dk": (q, xp, v), "dv": (q, k, xp)}[name]
+            args_m = {"dq": (xm, k, v), "dk": (q, xm, v), "dv": (q, k, xm)}[name]
+            fd = (loss(*args_p) - loss(*args_m)) / (2 * eps)
+            assert g[idx] == pytest.approx(fd, rel=2e-6, abs=2e-8), (name, idx)
+
+
+def test_gqa_with_one_group_per_head_is_ordinary_attention():
+    q, k, v, dout = (_rand(s, 2, 3, 7, 4) for s in (21, 22, 23, 24))
+    o1, l1 = oracle.attention_fwd(q, k, v, 0.5, True)
+    o2, l2 = oracle.attention_fwd_gqa(q, k, v, 0.5, True)
+    assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+    r1, r2 = oracle.attention_bwd(q, k, v, dout, 0.5, True), oracle.attention_bwd_gqa(q, k, v, dout, 0.5, True)
+    for key in ("dq", "dk", "dv"):
+        assert np.array_equal(r1[key], r2[key])
