@@ -120,6 +120,30 @@ int fa_bwd(const void* q, const void* k, const void* v, const void* o, const flo
            int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
 
 /*
+ * Multi-query / grouped-query attention (section 3.1, "Attention variants": the tensor
+ * indexing changes, K and V are not duplicated in HBM).  q, o, dout, dq are [B,H,N,d] and
+ * lse is [B,H,N] as above; k, v, dk, dv are [B,H_kv,N,d] (FP8: k_scale, v_scale are
+ * [B,H_kv,ceil(N/block_rows)]), with H_kv >= 1 dividing H (else FA_ERR_SHAPE).  Query head h
+ * reads key/value head h / (H / H_kv): consecutive query heads form a group.  dk and dv are
+ * the sums over the query heads of a group, accumulated on chip in a fixed order (no
+ * atomics).  H_kv == H is exactly fa_fwd / fa_fwd_fp8 / fa_bwd.  The workspace size is
+ * fa_bwd_workspace_bytes(B, H, N, d, dtype), as for fa_bwd.  Everything else (dtypes, head
+ * dimensions, alignment, errors) is as documented for the entry point of the same name
+ * without the suffix.
+ */
+int fa_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse,
+               int B, int H, int H_kv, int N, int d, float scale, int causal, int dtype, void* stream);
+
+int fa_fwd_fp8_gqa(const void* q8, const void* k8, const void* v8,
+                   const float* q_scale, const float* k_scale, const float* v_scale,
+                   void* o, float* lse, int B, int H, int H_kv, int N, int d, int block_rows,
+                   float scale, int causal, void* stream);
+
+int fa_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const float* lse,
+               const void* dout, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
+               int B, int H, int H_kv, int N, int d, float scale, int causal, int dtype, void* stream);
+
+/*
  * Measurement aid, not part of the attention path: the rate of the matrix pipes alone.  The
  * roofline fractions of the kernels above are quoted against the published MFMA peak; this
  * call measures what the chip sustains when every wave issues only independent MFMAs

@@ -17,7 +17,7 @@ FA_F32, FA_BF16, FA_F16, FA_FP8_E4M3 = 0, 1, 2, 3
 _DTYPE_CODE = {torch.float32: FA_F32, torch.bfloat16: FA_BF16, torch.float16: FA_F16}
 
 EXPORTS = ("fa_fwd", "fa_fwd_fp8", "fa_fp8_quant_hadamard", "fa_bwd_workspace_bytes", "fa_bwd",
-           "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
+           "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
 
 _lib = None
 
@@ -47,6 +47,12 @@ def lib():
         L.fa_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.fa_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_bwd.restype = ci
+        L.fa_fwd_gqa.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, ci, cf, ci, ci, vp]
+        L.fa_fwd_gqa.restype = ci
+        L.fa_fwd_fp8_gqa.argtypes = [vp, vp, vp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, cf, ci, vp]
+        L.fa_fwd_fp8_gqa.restype = ci
+        L.fa_bwd_gqa.argtypes = [vp] * 10 + [ctypes.c_size_t, ci, ci, ci, ci, ci, cf, ci, ci, vp]
+        L.fa_bwd_gqa.restype = ci
         L.fa_probe_mfma_flops.argtypes = [ci, ci]
         L.fa_probe_mfma_flops.restype = ctypes.c_double
         L.fa_probe_mfma.argtypes = [vp, ctypes.c_size_t, fp, ci, ci, vp]
@@ -141,6 +147,60 @@ def fa_bwd(q, k, v, o, lse, dout, scale, causal, dq=None, dk=None, dv=None, work
                       B, H, N, d, float(scale), int(bool(causal)), code, _stream())
     if st != FA_OK:
         raise FaError(st, "fa_bwd")
+    return dq, dk, dv
+
+
+def fa_fwd_gqa(q, k, v, scale, causal, o=None, lse=None, dtype=None):
+    """Grouped-query forward: q [B,H,N,d]; k, v [B,H_kv,N,d] with H_kv dividing H."""
+    _check_dev(q, k, v, o, lse)
+    B, H, N, d = q.shape
+    H_kv = k.shape[1]
+    code = dtype if dtype is not None else _DTYPE_CODE[q.dtype]
+    if o is None:
+        o = torch.empty((B, H, N, d), device=q.device, dtype=torch.bfloat16 if code == FA_FP8_E4M3 else q.dtype)
+    if lse is None:
+        lse = torch.empty((B, H, N), device=q.device, dtype=torch.float32)
+    st = lib().fa_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, H_kv, N, d,
+                          float(scale), int(bool(causal)), code, _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_fwd_gqa")
+    return o, lse
+
+
+def fa_fwd_fp8_gqa(q8, k8, v8, q_scale, k_scale, v_scale, scale, causal, block_rows=128, o=None, lse=None):
+    """Grouped-query FP8 forward: q8 [B,H,N,d]; k8, v8 [B,H_kv,N,d] and their scales [B,H_kv,blocks]."""
+    _check_dev(q8, k8, v8, q_scale, k_scale, v_scale, o, lse)
+    B, H, N, d = q8.shape
+    H_kv = k8.shape[1]
+    if o is None:
+        o = torch.empty((B, H, N, d), device=q8.device, dtype=torch.bfloat16)
+    if lse is None:
+        lse = torch.empty((B, H, N), device=q8.device, dtype=torch.float32)
+    st = lib().fa_fwd_fp8_gqa(q8.data_ptr(), k8.data_ptr(), v8.data_ptr(), q_scale.data_ptr(), k_scale.data_ptr(),
+                              v_scale.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, H_kv, N, d, int(block_rows),
+                              float(scale), int(bool(causal)), _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_fwd_fp8_gqa")
+    return o, lse
+
+
+def fa_bwd_gqa(q, k, v, o, lse, dout, scale, causal, dq=None, dk=None, dv=None, workspace=None):
+    """Grouped-query backward: dQ [B,H,N,d]; dK, dV [B,H_kv,N,d] (summed over each group's query heads)."""
+    _check_dev(q, k, v, o, lse, dout, dq, dk, dv, workspace)
+    B, H, N, d = q.shape
+    H_kv = k.shape[1]
+    code = _DTYPE_CODE[q.dtype]
+    need = fa_bwd_workspace_bytes(B, H, N, d, code)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), device=q.device, dtype=torch.uint8)
+    dq = torch.empty_like(q) if dq is None else dq
+    dk = torch.empty_like(k) if dk is None else dk
+    dv = torch.empty_like(v) if dv is None else dv
+    st = lib().fa_bwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), dout.data_ptr(),
+                          dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                          B, H, H_kv, N, d, float(scale), int(bool(causal)), code, _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_bwd_gqa")
     return dq, dk, dv
 
 

@@ -40,33 +40,58 @@ const char* fa_status_string(int status) {
     }
 }
 
-int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, float scale,
-           int causal, int dtype, void* stream) {
+static int fwd_any(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
+                   int d, float scale, int causal, int dtype, void* stream) {
     if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
     if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
     int st = check_common(B, H, N, d, scale, causal);
     if (st != FA_OK) return st;
+    if (H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (dtype) {
-        case FA_F32: return fa::launch_fwd_f32(q, k, v, o, lse, B, H, N, d, scale, causal, s);
-        case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, N, d, scale, causal, s);
-        case FA_F16: return fa::launch_fwd_f16(q, k, v, o, lse, B, H, N, d, scale, causal, s);
-        default: return fa::launch_fwd_fp8(q, k, v, nullptr, nullptr, nullptr, o, lse, B, H, N, d, scale, causal, s);
+        case FA_F32: return fa::launch_fwd_f32(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
+        case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
+        case FA_F16: return fa::launch_fwd_f16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
+        default:
+            return fa::launch_fwd_fp8(q, k, v, nullptr, nullptr, nullptr, o, lse, B, H, H_kv, N, d, scale, causal, s);
     }
+}
+
+static int fwd_fp8_any(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
+                       const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d,
+                       int block_rows, float scale, int causal, void* stream) {
+    if (!q8 || !k8 || !v8 || !q_scale || !k_scale || !v_scale || !o || !lse) return FA_ERR_NULL;
+    int st = check_common(B, H, N, d, scale, causal);
+    if (st != FA_OK) return st;
+    if (block_rows <= 0 || H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
+    if (block_rows != 128) return FA_ERR_UNSUPPORTED;
+    if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
+    return fa::launch_fwd_fp8(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, d, scale, causal,
+                              static_cast<hipStream_t>(stream));
+}
+
+int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, float scale,
+           int causal, int dtype, void* stream) {
+    return fwd_any(q, k, v, o, lse, B, H, H, N, d, scale, causal, dtype, stream);
+}
+
+int fa_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
+               float scale, int causal, int dtype, void* stream) {
+    return fwd_any(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, dtype, stream);
 }
 
 int fa_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
                const float* v_scale, void* o, float* lse, int B, int H, int N, int d, int block_rows, float scale,
                int causal, void* stream) {
-    if (!q8 || !k8 || !v8 || !q_scale || !k_scale || !v_scale || !o || !lse) return FA_ERR_NULL;
-    int st = check_common(B, H, N, d, scale, causal);
-    if (st != FA_OK) return st;
-    if (block_rows <= 0) return FA_ERR_SHAPE;
-    if (block_rows != 128) return FA_ERR_UNSUPPORTED;
-    if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
-    return fa::launch_fwd_fp8(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, d, scale, causal,
-                              static_cast<hipStream_t>(stream));
+    return fwd_fp8_any(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H, N, d, block_rows, scale, causal, stream);
+}
+
+int fa_fwd_fp8_gqa(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
+                   const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d, int block_rows,
+                   float scale, int causal, void* stream) {
+    return fwd_fp8_any(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, d, block_rows, scale, causal,
+                       stream);
 }
 
 int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales, int B, int H, int N, int d,
@@ -89,21 +114,36 @@ size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype) {
     return fa::bwd_workspace_bytes(B, H, N, d);
 }
 
-int fa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout, void* dq,
-           void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, float scale,
-           int causal, int dtype, void* stream) {
+static int bwd_any(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int H_kv, int N,
+                   int d, float scale, int causal, int dtype, void* stream) {
     if (!q || !k || !v || !o || !lse || !dout || !dq || !dk || !dv) return FA_ERR_NULL;
     if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
     int st = check_common(B, H, N, d, scale, causal);
     if (st != FA_OK) return st;
+    if (H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
     if (d != 128 || (dtype != FA_BF16 && dtype != FA_F16)) return FA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dout) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
         return FA_ERR_ALIGN;
     if (!workspace || workspace_bytes < fa::bwd_workspace_bytes(B, H, N, d)) return FA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FA_ERR_ALIGN;
-    return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, N, d, scale, causal, dtype,
+    return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, d, scale, causal, dtype,
                           static_cast<hipStream_t>(stream));
+}
+
+int fa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout, void* dq,
+           void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int N, int d, float scale,
+           int causal, int dtype, void* stream) {
+    return bwd_any(q, k, v, o, lse, dout, dq, dk, dv, workspace, workspace_bytes, B, H, H, N, d, scale, causal, dtype,
+                   stream);
+}
+
+int fa_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+               void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int H_kv, int N,
+               int d, float scale, int causal, int dtype, void* stream) {
+    return bwd_any(q, k, v, o, lse, dout, dq, dk, dv, workspace, workspace_bytes, B, H, H_kv, N, d, scale, causal,
+                   dtype, stream);
 }
 
 double fa_probe_mfma_flops(int dtype, int iters) {

@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(256, 1)
 fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
               const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
               uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
-              int n_kblocks, int total_wg, float scale) {
+              int n_kblocks, int total_wg, int kv_group, float scale) {
     constexpr int D = kBwdD;
     constexpr int BK = 128;        // keys per workgroup
     constexpr int BQ = 64;         // queries per loop iteration
@@ -90,13 +90,10 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     const int kb = id % n_kblocks;  // causal: key block 0 has the longest loop and comes first
     const int key0 = kb * BK;
 
+    // bh counts key/value heads; the kv_group query heads that share this one are bh * kv_group + g
     const size_t head_off = (size_t)bh * N * D;
-    const uint16_t* qh = q + head_off;
     const uint16_t* kh = k + head_off;
     const uint16_t* vh = v + head_off;
-    const uint16_t* doh = dout + head_off;
-    const float* lh = lse + (size_t)bh * N;
-    const float* dh = dvec + (size_t)bh * N;
     const float sc = scale * kLog2e;
 
     // ---- this wave's K and V rows as B operands (lane: key column, 8 head-dim elements)
@@ -126,6 +123,22 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
 
     const int n_qtiles = (N + BQ - 1) / BQ;
     const int it0 = CAUSAL ? key0 / BQ : 0;  // first query tile that can see this key block
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+    // Masked query tiles come first: every tile when the key block is ragged (keys past N), else
+    // the tiles on the causal diagonal.  They get a loop of their own so that the main loop has a
+    // single straight-line body.
+    const int it_masked_end = key0 + BK > N ? n_qtiles : (CAUSAL ? min(n_qtiles, (key0 + BK - 1) / BQ + 1) : it0);
+
+    // Every query head of the group adds into the same dK_j, dV_j (grouped-query attention: the
+    // gradient of a shared key/value head is the sum over the query heads that read it).
+#pragma nounroll
+    for (int g = 0; g < kv_group; ++g) {
+    const size_t qhead = (size_t)bh * kv_group + g;
+    const uint16_t* qh = q + qhead * N * D;
+    const uint16_t* doh = dout + qhead * N * D;
+    const float* lh = lse + qhead * N;
+    const float* dh = dvec + qhead * N;
 
     // Q_i and dO_i tiles are contiguous runs of the row-major tensors; rows past N lie outside the
     // buffer resources and read as zero.
@@ -165,14 +178,6 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         store_tile(0);
     }
     __syncthreads();
-
-    const int tr_row = (lane & 15) >> 2;
-    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
-
-    // Masked query tiles come first: every tile when the key block is ragged (keys past N), else
-    // the tiles on the causal diagonal.  They get a loop of their own so that the main loop has a
-    // single straight-line body.
-    const int it_masked_end = key0 + BK > N ? n_qtiles : (CAUSAL ? min(n_qtiles, (key0 + BK - 1) / BQ + 1) : it0);
 
     auto iteration = [&](int it, auto mask_tag) {
         const int st = (it - it0) & 1;
@@ -299,6 +304,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     int it = it0;
     for (; it < it_masked_end; ++it) iteration(it, std::true_type{});
     for (; it < n_qtiles; ++it) iteration(it, std::false_type{});
+    }  // query heads of the group
 
     // ---- epilogue: dK_j = scale * acc, dV_j = acc  (rows = keys 8g+4h+r of this wave, col = d)
 #pragma unroll
@@ -320,7 +326,7 @@ template <typename Tag, int BC, int NW, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, 2)
 fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
-                 uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, float scale) {
+                 uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, int kv_group, float scale) {
     constexpr int D = kBwdD;
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
@@ -348,8 +354,9 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
 
     const size_t head_off = (size_t)bh * N * D;
-    const uint16_t* kh = k + head_off;
-    const uint16_t* vh = v + head_off;
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
+    const uint16_t* kh = k + kv_off;
+    const uint16_t* vh = v + kv_off;
     const int wave_q0 = qt * BR + wave * 32;
     const int qi = wave_q0 + col;
     const int qrow = min(qi, N - 1);  // rows past N compute a copy of row N-1, never stored
@@ -489,8 +496,8 @@ size_t bwd_workspace_bytes(int B, int H, int N, int d) {
 
 template <typename Tag>
 static int launch_bwd_t(const void* q, const void* k, const void* v, const void* o, const float* lse,
-                        const void* dout, void* dq, void* dk, void* dv, void* workspace, int B, int H, int N,
-                        float scale, int causal, hipStream_t stream) {
+                        const void* dout, void* dq, void* dk, void* dv, void* workspace, int B, int H, int H_kv,
+                        int N, float scale, int causal, hipStream_t stream) {
     const long rows = (long)B * H * N;
     float* dvec = static_cast<float*>(workspace);
     auto u16 = [](const void* p) { return static_cast<const uint16_t*>(p); };
@@ -499,16 +506,16 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
                        u16(o), u16(dout), dvec, rows);
 
     int n_kblocks = (N + 127) / 128;
-    long total = (long)B * H * n_kblocks;
+    long total = (long)B * H_kv * n_kblocks;
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     if (causal)
         hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
-                           static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, scale);
+                           static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
-                           static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, scale);
+                           static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
 
     constexpr int BC = 64, NW = 8;
     int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
@@ -516,22 +523,22 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
     if (causal)
         hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, true>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
                            u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
-                           (int)total_q, scale);
+                           (int)total_q, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, false>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
                            u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
-                           (int)total_q, scale);
+                           (int)total_q, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
 int launch_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
-               void* dq, void* dk, void* dv, void* workspace, int B, int H, int N, int d, float scale, int causal,
-               int dtype, hipStream_t stream) {
+               void* dq, void* dk, void* dv, void* workspace, int B, int H, int H_kv, int N, int d, float scale,
+               int causal, int dtype, hipStream_t stream) {
     if (d != kBwdD) return FA_ERR_UNSUPPORTED;
     if (dtype == FA_BF16)
-        return launch_bwd_t<bf16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, N, scale, causal, stream);
+        return launch_bwd_t<bf16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, scale, causal, stream);
     if (dtype == FA_F16)
-        return launch_bwd_t<f16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, N, scale, causal, stream);
+        return launch_bwd_t<f16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, scale, causal, stream);
     return FA_ERR_UNSUPPORTED;
 }
 

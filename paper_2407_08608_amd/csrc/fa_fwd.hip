@@ -47,7 +47,7 @@ template <typename Tag, int D, int BC, int NW, int RQ, int PD, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, (RQ == 1 && D <= 128) ? 2 : 1)
 fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
-                    int N, int n_qtiles, int total_wg, float scale) {
+                    int N, int n_qtiles, int total_wg, int kv_group, float scale) {
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32 * RQ;
     constexpr int KSTR = D + 8;   // +16 B per row: 128-bit row reads hit distinct banks
@@ -72,9 +72,10 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
 
     const size_t head_off = (size_t)bh * N * D;
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
     const uint16_t* qh = q + head_off;
-    const uint16_t* kh = k + head_off;
-    const uint16_t* vh = v + head_off;
+    const uint16_t* kh = k + kv_off;
+    const uint16_t* vh = v + kv_off;
 
     const int wave_q0 = qt * BR + wave * (32 * RQ);
     const float sc = scale * kLog2e;  // exp(scale*s - scale*m) = exp2(sc*s - sc*m)
@@ -339,7 +340,7 @@ template <typename Tag, int BC, int P, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2)
 fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
-                       int N, int n_qtiles, int total_wg, float scale) {
+                       int N, int n_qtiles, int total_wg, int kv_group, float scale) {
     constexpr int D = 128;
     constexpr int BR = 256;
     constexpr int NS = 4;              // LDS stages per tensor
@@ -397,8 +398,9 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
 
     // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
-    const BufferWords k_rsrc = make_buffer_words(k + head_off, (uint32_t)N * D * 2);
-    const BufferWords v_rsrc = make_buffer_words(v + head_off, (uint32_t)N * D * 2);
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
+    const BufferWords k_rsrc = make_buffer_words(k + kv_off, (uint32_t)N * D * 2);
+    const BufferWords v_rsrc = make_buffer_words(v + kv_off, (uint32_t)N * D * 2);
     const int st_row = 4 * wave + (lane >> 4), st_pos = lane & 15;
     const int k_src = st_row * ROWB + ((st_pos ^ (st_row & 15)) << 4);        // byte offset within a tile
     const int v_src = st_row * ROWB + ((st_pos ^ ((st_row & 3) << 2)) << 4);
@@ -630,13 +632,15 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
 template <int D, int BC, bool CAUSAL>
 __global__ void __launch_bounds__(64) fa_fwd_f32_kernel(const float* __restrict__ q, const float* __restrict__ k,
                                                         const float* __restrict__ v, float* __restrict__ o,
-                                                        float* __restrict__ lse, int N, int n_qtiles, float scale) {
+                                                        float* __restrict__ lse, int N, int n_qtiles, int kv_group,
+                                                        float scale) {
     constexpr int BR = 64;
     __shared__ float lds_k[BC * D];
     __shared__ float lds_v[BC * D];
     const int tid = threadIdx.x;
     const int bh = blockIdx.x / n_qtiles, qt = blockIdx.x % n_qtiles;
     const size_t head_off = (size_t)bh * N * D;
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;
     const int qi = qt * BR + tid;
     const float sc = scale * kLog2e;
 
@@ -654,8 +658,8 @@ __global__ void __launch_bounds__(64) fa_fwd_f32_kernel(const float* __restrict_
         __syncthreads();
         for (int e = tid; e < BC * D; e += 64) {
             int key = key0 + e / D;
-            lds_k[e] = key < N ? k[head_off + (size_t)key0 * D + e] : 0.f;
-            lds_v[e] = key < N ? v[head_off + (size_t)key0 * D + e] : 0.f;
+            lds_k[e] = key < N ? k[kv_off + (size_t)key0 * D + e] : 0.f;
+            lds_v[e] = key < N ? v[kv_off + (size_t)key0 * D + e] : 0.f;
         }
         __syncthreads();
         float s[BC];
@@ -695,7 +699,7 @@ __global__ void __launch_bounds__(64) fa_fwd_f32_kernel(const float* __restrict_
 
 // ---------------------------------------------------------------------------------------
 template <typename Tag, int D, int BC, int NW, int RQ, int PD>
-static int launch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+static int launch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                         float scale, int causal, hipStream_t stream) {
     constexpr int BR = NW * 32 * RQ;
     int n_qtiles = (N + BR - 1) / BR;
@@ -708,15 +712,15 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
     auto op = static_cast<uint16_t*>(o);
     if (causal)
         hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, PD, true>), grid, block, 0, stream, qp, kp, vp,
-                           op, lse, N, n_qtiles, (int)total, scale);
+                           op, lse, N, n_qtiles, (int)total, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_fwd_16bit_kernel<Tag, D, BC, NW, RQ, PD, false>), grid, block, 0, stream, qp, kp, vp,
-                           op, lse, N, n_qtiles, (int)total, scale);
+                           op, lse, N, n_qtiles, (int)total, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
 template <typename Tag>
-static int launch_pingpong(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+static int launch_pingpong(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                            float scale, int causal, hipStream_t stream) {
     constexpr int BR = 256, BC = 64, P = 4;
     int n_qtiles = (N + BR - 1) / BR;
@@ -729,10 +733,10 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
     auto op = static_cast<uint16_t*>(o);
     if (causal)
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, (int)total, scale);
+                           n_qtiles, (int)total, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, (int)total, scale);
+                           n_qtiles, (int)total, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
@@ -745,32 +749,32 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
 //   d = 256: the 128-register output accumulator allows only one wave per SIMD, so the operand
 //     reads are software-pipelined eight MFMA steps ahead instead.
 template <typename Tag>
-static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N,
+static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                           int d, float scale, int causal, hipStream_t stream) {
     const bool small_tile = causal ? (N <= 2048) : (N <= 512);
     switch (d) {
         case 64:
-            if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 128:
-            if (small_tile) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-            return launch_pingpong<Tag>(q, k, v, o, lse, B, H, N, scale, causal, stream);
-        case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, N, scale, causal, stream);
+            if (small_tile) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }
 
-int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                     float scale, int causal, hipStream_t stream) {
-    return dispatch_16bit<bf16_tag>(q, k, v, o, lse, B, H, N, d, scale, causal, stream);
+    return dispatch_16bit<bf16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, stream);
 }
 
-int launch_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+int launch_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                    float scale, int causal, hipStream_t stream) {
-    return dispatch_16bit<f16_tag>(q, k, v, o, lse, B, H, N, d, scale, causal, stream);
+    return dispatch_16bit<f16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, stream);
 }
 
-int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                    float scale, int causal, hipStream_t stream) {
     if (d != 64) return FA_ERR_UNSUPPORTED;
     constexpr int BR = 64;
@@ -784,10 +788,10 @@ int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* 
     auto op = static_cast<float*>(o);
     if (causal)
         hipLaunchKernelGGL((fa_fwd_f32_kernel<64, 32, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N, n_qtiles,
-                           scale);
+                           H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_fwd_f32_kernel<64, 32, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, scale);
+                           n_qtiles, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 

@@ -40,7 +40,7 @@ __global__ void __launch_bounds__(NW * 64, D <= 128 ? 2 : 1)
 fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
                   const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                   const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
-                  int n_qtiles, int total_wg, int n_sblocks, float scale) {
+                  int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
     constexpr int KSTR = D + 16;  // bytes per LDS row
@@ -68,8 +68,9 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 
     const size_t head_off = (size_t)bh * N * D;
     const uint8_t* qh = q + head_off;
-    const uint8_t* kh = k + head_off;
-    const uint8_t* vh = v + head_off;
+    const int kv_bh = bh / kv_group;  // grouped-query: kv_group query heads per K/V head
+    const uint8_t* kh = k + (size_t)kv_bh * N * D;
+    const uint8_t* vh = v + (size_t)kv_bh * N * D;
     const int wave_q0 = qt * BR + wave * 32;
 
     float sq = 1.0f;
@@ -141,8 +142,8 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         if (wave_active) {
             float sk = 1.0f, sv_new = 1.0f;
             if constexpr (SCALED) {
-                sk = k_scale[(size_t)bh * n_sblocks + key0 / 128];
-                sv_new = v_scale[(size_t)bh * n_sblocks + key0 / 128];
+                sk = k_scale[(size_t)kv_bh * n_sblocks + key0 / 128];
+                sv_new = v_scale[(size_t)kv_bh * n_sblocks + key0 / 128];
             }
             const float sc = sc_q * sk;
 
@@ -260,7 +261,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 
 template <int D, int BC, int NW>
 static int launch_fp8(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
-                      const float* vs, void* o, float* lse, int B, int H, int N, float scale, int causal,
+                      const float* vs, void* o, float* lse, int B, int H, int H_kv, int N, float scale, int causal,
                       hipStream_t stream) {
     constexpr int BR = NW * 32;
     int n_qtiles = (N + BR - 1) / BR;
@@ -275,7 +276,7 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
     const bool scaled = qs != nullptr;
 #define FA_LAUNCH_FP8(C, S)                                                                                       \
     hipLaunchKernelGGL((fa_fwd_fp8_kernel<D, BC, NW, C, S>), grid, block, 0, stream, qp, kp, vp, qs, ks, vs, op, \
-                       lse, N, n_qtiles, (int)total, n_sblocks, scale)
+                       lse, N, n_qtiles, (int)total, n_sblocks, H / H_kv, scale)
     if (causal) {
         if (scaled) FA_LAUNCH_FP8(true, true); else FA_LAUNCH_FP8(true, false);
     } else {
@@ -286,17 +287,17 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
 }
 
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
-                   const float* v_scale, void* o, float* lse, int B, int H, int N, int d, float scale, int causal,
+                   const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d, float scale, int causal,
                    hipStream_t stream) {
     const bool small_tile = causal ? (N <= 2048) : (N <= 512);
     switch (d) {
         case 64:
-            if (small_tile) return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
-            return launch_fp8<64, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+            if (small_tile) return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+            return launch_fp8<64, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 128:
-            if (small_tile) return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
-            return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
-        case 256: return launch_fp8<256, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, N, scale, causal, stream);
+            if (small_tile) return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+            return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case 256: return launch_fp8<256, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }
