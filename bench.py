@@ -238,8 +238,7 @@ def extra_table(torch, binding, inputs, dev):
                 table[f"fwd_fp8_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
                     "ms": round(ms, 4), "tflops": tf(B, H, N, d, causal, ms),
                     "frac_of_fp8_peak": round(tf(B, H, N, d, causal, ms) / PEAK_FP8_TFLOPS, 4)}
-    d = 128  # bf16 backward
-    for N in (1024, 4096, 16384):
+    for d, N in ((128, 1024), (128, 4096), (128, 16384), (64, 4096), (64, 16384)):  # bf16 backward
         B, H = inputs.benchmark_shape(N, d)
         q, k, v, do = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(4))
         ws = torch.empty(binding.fa_bwd_workspace_bytes(B, H, N, d), device=dev, dtype=torch.uint8)

@@ -1,4 +1,4 @@
-// Backward attention for gfx950, head dimension 128, bf16 / fp16 (paper section 2.1 chain rule,
+// Backward attention for gfx950, head dimensions 64 and 128, bf16 / fp16 (paper section 2.1 chain rule,
 // Algorithm 3's recomputation of P from L and its D = rowsum(dO o O)).
 //
 //   preprocess : D = rowsum(dO o O) per query row (HBM-bound)
@@ -27,18 +27,22 @@
 
 namespace fa {
 
-constexpr int kBwdD = 128;
 constexpr int kPipe = 2;  // MFMA steps by which LDS operand reads lead their use
 
+// LDS row stride (elements) of tiles that are read both by rows and transposed: an odd multiple
+// of 16 bytes keeps the row reads conflict-free, and the offset from a multiple of 256 bytes
+// decides how much the four rows of a transposing read overlap in the banks.
+constexpr int bwd_row_stride(int d) { return d == 128 ? d + 24 : d + 40; }
+
 // ---------------------------------------------------------------------------------------
-template <typename Tag>
+template <typename Tag, int D>
 __global__ void __launch_bounds__(256)
 fa_bwd_preprocess_kernel(const uint16_t* __restrict__ o, const uint16_t* __restrict__ dout,
                          float* __restrict__ dvec, long rows) {
-    constexpr int D = kBwdD;
+    constexpr int LPR = D / 8;  // lanes per row, 8 elements each
     using E = Elem<Tag>;
-    const int lane16 = threadIdx.x & 15;
-    long row = (long)blockIdx.x * 16 + (threadIdx.x >> 4);
+    const int lane16 = threadIdx.x & (LPR - 1);
+    long row = (long)blockIdx.x * (256 / LPR) + threadIdx.x / LPR;
     float acc = 0.f;
     if (row < rows) {
         i32x4 a = *reinterpret_cast<const i32x4*>(o + row * D + lane16 * 8);
@@ -51,25 +55,24 @@ fa_bwd_preprocess_kernel(const uint16_t* __restrict__ o, const uint16_t* __restr
         }
     }
 #pragma unroll
-    for (int off = 8; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (row < rows && lane16 == 0) dvec[row] = acc;
 }
 
 // ---------------------------------------------------------------------------------------
-template <typename Tag, bool CAUSAL>
-__global__ void __launch_bounds__(256, 1)
+template <typename Tag, int D, bool CAUSAL>
+__global__ void __launch_bounds__(256, D == 128 ? 1 : 2)
 fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
               const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
               uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
               int n_kblocks, int total_wg, int kv_group, float scale) {
-    constexpr int D = kBwdD;
     constexpr int BK = 128;        // keys per workgroup
     constexpr int BQ = 64;         // queries per loop iteration
     constexpr int NT = 256;
     // Row stride of the Q and dO tiles: they are read both as rows (128-bit) and transposed.
-    // Measured LDS rates per CU: 304 B gives 211 / 123 B/clk (rows / transposed), 272 B gives
-    // 208 / 63, 320 B gives 63 / 208.
-    constexpr int RSTR = D + 24;
+    // Measured LDS rates per CU at D = 128: 304 B gives 211 / 123 B/clk (rows / transposed), 272 B
+    // gives 208 / 63, 320 B gives 63 / 208.
+    constexpr int RSTR = bwd_row_stride(D);
     constexpr int KS = D / 16;
     constexpr int DT = D / 32;
     constexpr int CPR = D / 8;     // 16-byte chunks per row
@@ -109,8 +112,10 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     // half of the register file, which only MFMA can address directly.  K_j / V_j operands and the
     // dK / dV accumulators are touched by MFMA alone: pin the operands there so that the score
     // tiles, which the exponentials read, stay in ordinary registers and need no copies.
+    if constexpr (D == 128) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(kreg[ks]), "+a"(vreg[ks]));
+        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(kreg[ks]), "+a"(vreg[ks]));
+    }
 
     f32x16 dkacc[DT], dvacc[DT];
 #pragma unroll
@@ -253,9 +258,15 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                     pacc[sub] = E::mma(a1, vreg[ks], ks == 0 ? zero : pacc[sub]);
                     if (sub == 0 && ks == KS - 1) fetch_ld(0, 0);
                     if (sub == 1) {
-                        if (ks % 2 == 1 && ks / 2 + 1 < 4) fetch_ld(0, ks / 2 + 1);
+                        // the 8 register pairs of sub-tile 0 spread over the KS steps; the L, D group
+                        // of a pair is fetched one step before the step that needs it first
+                        constexpr int PP = 8 / KS;
+#pragma unroll
+                        for (int g = 1; g < 4; ++g)
+                            if ((2 * g) / PP == ks + 1) fetch_ld(0, g);
                         if (ks == KS - 1) fetch_ld(1, 0);
-                        softmax_pair(0, ks);
+#pragma unroll
+                        for (int p = 0; p < PP; ++p) softmax_pair(0, ks * PP + p);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -289,8 +300,12 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                     dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
                     dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
                     if (sub == 0) {
-                        if (u % 2 == 1 && u / 2 + 1 < 4) fetch_ld(1, u / 2 + 1);
-                        softmax_pair(1, u);
+                        constexpr int PP = 8 / (2 * DT);
+#pragma unroll
+                        for (int g = 1; g < 4; ++g)
+                            if ((2 * g) / PP == u + 1) fetch_ld(1, g);
+#pragma unroll
+                        for (int p = 0; p < PP; ++p) softmax_pair(1, u * PP + p);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -322,16 +337,15 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
 
 // ---------------------------------------------------------------------------------------
 // dQ pass: the forward kernel's structure with dO alongside Q and K^T in place of V^T.
-template <typename Tag, int BC, int NW, bool CAUSAL>
+template <typename Tag, int D, int BC, int NW, bool CAUSAL>
 __global__ void __launch_bounds__(NW * 64, 2)
 fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
                  uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, int kv_group, float scale) {
-    constexpr int D = kBwdD;
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
-    constexpr int RSTR = D + 24;  // K tile: row reads and transposed reads (304 B)
-    constexpr int VSTR = D + 8;   // V tile: row reads only (272 B)
+    constexpr int RSTR = bwd_row_stride(D);  // K tile: row reads and transposed reads
+    constexpr int VSTR = D + 8;              // V tile: row reads only
     constexpr int KT = BC / 32;
     constexpr int KS = D / 16;
     constexpr int DT = D / 32;
@@ -494,7 +508,7 @@ size_t bwd_workspace_bytes(int B, int H, int N, int d) {
     return (rows * sizeof(float) + 15) & ~(size_t)15;  // D = rowsum(dO o O)
 }
 
-template <typename Tag>
+template <typename Tag, int D>
 static int launch_bwd_t(const void* q, const void* k, const void* v, const void* o, const float* lse,
                         const void* dout, void* dq, void* dk, void* dv, void* workspace, int B, int H, int H_kv,
                         int N, float scale, int causal, hipStream_t stream) {
@@ -502,18 +516,20 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
     float* dvec = static_cast<float*>(workspace);
     auto u16 = [](const void* p) { return static_cast<const uint16_t*>(p); };
 
-    hipLaunchKernelGGL((fa_bwd_preprocess_kernel<Tag>), dim3((unsigned)((rows + 15) / 16)), dim3(256), 0, stream,
+    constexpr int kRowsPerWg = 256 / (D / 8);
+    hipLaunchKernelGGL((fa_bwd_preprocess_kernel<Tag, D>), dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)),
+                       dim3(256), 0, stream,
                        u16(o), u16(dout), dvec, rows);
 
     int n_kblocks = (N + 127) / 128;
     long total = (long)B * H_kv * n_kblocks;
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     if (causal)
-        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
     else
-        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
 
@@ -521,11 +537,11 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
     int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
     long total_q = (long)B * H * n_qtiles;
     if (causal)
-        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, true>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
+        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, D, BC, NW, true>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
                            u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
                            (int)total_q, H / H_kv, scale);
     else
-        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, BC, NW, false>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
+        hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, D, BC, NW, false>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
                            u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,
                            (int)total_q, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
@@ -534,11 +550,13 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
 int launch_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
                void* dq, void* dk, void* dv, void* workspace, int B, int H, int H_kv, int N, int d, float scale,
                int causal, int dtype, hipStream_t stream) {
-    if (d != kBwdD) return FA_ERR_UNSUPPORTED;
-    if (dtype == FA_BF16)
-        return launch_bwd_t<bf16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, scale, causal, stream);
-    if (dtype == FA_F16)
-        return launch_bwd_t<f16_tag>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, scale, causal, stream);
+#define FA_BWD_CASE(TAG, DD) \
+    return launch_bwd_t<TAG, DD>(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, scale, causal, stream)
+    if (dtype == FA_BF16 && d == 128) FA_BWD_CASE(bf16_tag, 128);
+    if (dtype == FA_BF16 && d == 64) FA_BWD_CASE(bf16_tag, 64);
+    if (dtype == FA_F16 && d == 128) FA_BWD_CASE(f16_tag, 128);
+    if (dtype == FA_F16 && d == 64) FA_BWD_CASE(f16_tag, 64);
+#undef FA_BWD_CASE
     return FA_ERR_UNSUPPORTED;
 }
 

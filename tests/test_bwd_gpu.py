@@ -39,9 +39,10 @@ def _compare(got, ref, name):
 
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128])
 @pytest.mark.parametrize("N", [1, 40, 64, 129, 257, 600])
-def test_bwd_small_and_ragged(N, causal, dtype):
-    B, H, d = 2, 2, 128
+def test_bwd_small_and_ragged(N, d, causal, dtype):
+    B, H = 2, 2
     q, k, v = inputs.qkv(60 + N, B, H, N, d, dtype)
     dout = inputs.normal_tensor(61 + N, "do", (B, H, N, d), dtype)
     scale = d ** -0.5
@@ -81,10 +82,10 @@ def test_bwd_is_repeatable_and_workspace_checked():
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("N", [1024, 4096, 16384])
-def test_bwd_benchmark_shapes_sampled_heads(N, causal):
-    # 16k tokens, 16 heads of dim 128; the oracle differentiates whole (batch, head) slices
-    d = 128
+@pytest.mark.parametrize("N,d", [(1024, 128), (4096, 128), (16384, 128), (4096, 64), (16384, 64)])
+def test_bwd_benchmark_shapes_sampled_heads(N, d, causal):
+    # 16k tokens, hidden size 2048 (16 heads of dim 128 or 32 of dim 64); the oracle differentiates
+    # whole (batch, head) slices
     B, H = inputs.benchmark_shape(N, d)
     q, k, v = inputs.qkv(80, B, H, N, d, "bf16")
     dout = inputs.normal_tensor(81, "do", (B, H, N, d), "bf16")
