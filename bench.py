@@ -238,6 +238,16 @@ def extra_table(torch, binding, inputs, dev):
                 table[f"fwd_fp8_d{d}_N{N}_{'causal' if causal else 'full'}"] = {
                     "ms": round(ms, 4), "tflops": tf(B, H, N, d, causal, ms),
                     "frac_of_fp8_peak": round(tf(B, H, N, d, causal, ms) / PEAK_FP8_TFLOPS, 4)}
+    # scheduling ablation at the paper's shape (section 4.2: batch 4, seqlen 8448, 16 heads, d 128, fp16, non-causal)
+    B, H, N, d = 4, 16, 8448, 128
+    q, k, v = (torch.randn((B, H, N, d), device=dev, dtype=torch.float16) for _ in range(3))
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+    for name, sched in (("pingpong_async_staging", binding.FA_SCHED_PINGPONG),
+                        ("lockstep_8_waves", binding.FA_SCHED_LOCKSTEP_8W),
+                        ("lockstep_4_waves_2_workgroups", binding.FA_SCHED_LOCKSTEP_4W)):
+        ms = _time_call(torch, lambda: binding.fa_fwd_schedule(q, k, v, d ** -0.5, False, sched, o=o, lse=lse))
+        table[f"ablation_f16_b4_s8448_h16_d128_{name}"] = {"ms": round(ms, 4), "tflops": tf(B, H, N, d, False, ms)}
     for d, N in ((128, 1024), (128, 4096), (128, 16384), (64, 4096), (64, 16384)):  # bf16 backward
         B, H = inputs.benchmark_shape(N, d)
         q, k, v, do = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(4))

@@ -121,6 +121,25 @@ int fa_bwd(const void* q, const void* k, const void* v, const void* o, const flo
            int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
 
 /*
+ * Forward pass with the kernel schedule forced, for the scheduling ablation (section 4.2,
+ * "2-stage pipelining experiments", re-done with this chip's mechanisms).  Same contract as
+ * fa_fwd; FA_SCHED_AUTO is fa_fwd itself.  The other values need dtype FA_BF16 or FA_F16 and
+ * d = 128 (else FA_ERR_UNSUPPORTED); an unknown value is FA_ERR_SHAPE.
+ */
+typedef enum {
+    FA_SCHED_AUTO = 0,        /* the library's choice by shape */
+    FA_SCHED_LOCKSTEP_4W = 1, /* 128-query tile, 4 waves in lock-step, K/V staged through registers;
+                                 softmax/GEMM overlap only across two resident workgroups */
+    FA_SCHED_LOCKSTEP_8W = 2, /* 256-query tile, 8 waves in lock-step, K/V staged through registers */
+    FA_SCHED_PINGPONG = 3     /* 256-query tile, two wave groups alternating GEMMs and softmax,
+                                 K/V staged asynchronously into a 4-deep LDS ring */
+} fa_schedule;
+
+int fa_fwd_schedule(const void* q, const void* k, const void* v, void* o, float* lse,
+                    int B, int H, int N, int d, float scale, int causal, int dtype, int schedule,
+                    void* stream);
+
+/*
  * Multi-query / grouped-query attention (section 3.1, "Attention variants": the tensor
  * indexing changes, K and V are not duplicated in HBM).  q, o, dout, dq are [B,H,N,d] and
  * lse is [B,H,N] as above; k, v, dk, dv are [B,H_kv,N,d] (FP8: k_scale, v_scale are

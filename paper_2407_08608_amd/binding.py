@@ -17,7 +17,7 @@ FA_F32, FA_BF16, FA_F16, FA_FP8_E4M3 = 0, 1, 2, 3
 _DTYPE_CODE = {torch.float32: FA_F32, torch.bfloat16: FA_BF16, torch.float16: FA_F16}
 
 EXPORTS = ("fa_fwd", "fa_fwd_fp8", "fa_fp8_quant_hadamard", "fa_bwd_workspace_bytes", "fa_bwd",
-           "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
+           "fa_fwd_schedule", "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
 
 _lib = None
 
@@ -47,6 +47,8 @@ def lib():
         L.fa_bwd_workspace_bytes.restype = ctypes.c_size_t
         L.fa_bwd.argtypes = [vp] * 10 + [ctypes.c_size_t, ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_bwd.restype = ci
+        L.fa_fwd_schedule.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, cf, ci, ci, ci, vp]
+        L.fa_fwd_schedule.restype = ci
         L.fa_fwd_gqa.argtypes = [vp, vp, vp, vp, fp, ci, ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_fwd_gqa.restype = ci
         L.fa_fwd_fp8_gqa.argtypes = [vp, vp, vp, fp, fp, fp, vp, fp, ci, ci, ci, ci, ci, ci, cf, ci, vp]
@@ -148,6 +150,23 @@ def fa_bwd(q, k, v, o, lse, dout, scale, causal, dq=None, dk=None, dv=None, work
     if st != FA_OK:
         raise FaError(st, "fa_bwd")
     return dq, dk, dv
+
+
+FA_SCHED_AUTO, FA_SCHED_LOCKSTEP_4W, FA_SCHED_LOCKSTEP_8W, FA_SCHED_PINGPONG = 0, 1, 2, 3
+
+
+def fa_fwd_schedule(q, k, v, scale, causal, schedule, o=None, lse=None):
+    """fa_fwd with the kernel schedule forced (ablation)."""
+    _check_dev(q, k, v, o, lse)
+    B, H, N, d = q.shape
+    o = torch.empty_like(q) if o is None else o
+    if lse is None:
+        lse = torch.empty((B, H, N), device=q.device, dtype=torch.float32)
+    st = lib().fa_fwd_schedule(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, N, d,
+                               float(scale), int(bool(causal)), _DTYPE_CODE[q.dtype], int(schedule), _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_fwd_schedule")
+    return o, lse
 
 
 def fa_fwd_gqa(q, k, v, scale, causal, o=None, lse=None, dtype=None):

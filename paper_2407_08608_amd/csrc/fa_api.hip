@@ -41,18 +41,20 @@ const char* fa_status_string(int status) {
 }
 
 static int fwd_any(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
-                   int d, float scale, int causal, int dtype, void* stream) {
+                   int d, float scale, int causal, int dtype, int schedule, void* stream) {
     if (!q || !k || !v || !o || !lse) return FA_ERR_NULL;
     if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
     int st = check_common(B, H, N, d, scale, causal);
     if (st != FA_OK) return st;
     if (H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
+    if (schedule < FA_SCHED_AUTO || schedule > FA_SCHED_PINGPONG) return FA_ERR_SHAPE;
+    if (schedule != FA_SCHED_AUTO && dtype != FA_BF16 && dtype != FA_F16) return FA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (dtype) {
         case FA_F32: return fa::launch_fwd_f32(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
-        case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
-        case FA_F16: return fa::launch_fwd_f16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
+        case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, schedule, s);
+        case FA_F16: return fa::launch_fwd_f16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, schedule, s);
         default:
             return fa::launch_fwd_fp8(q, k, v, nullptr, nullptr, nullptr, o, lse, B, H, H_kv, N, d, scale, causal, s);
     }
@@ -73,12 +75,17 @@ static int fwd_fp8_any(const void* q8, const void* k8, const void* v8, const flo
 
 int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d, float scale,
            int causal, int dtype, void* stream) {
-    return fwd_any(q, k, v, o, lse, B, H, H, N, d, scale, causal, dtype, stream);
+    return fwd_any(q, k, v, o, lse, B, H, H, N, d, scale, causal, dtype, FA_SCHED_AUTO, stream);
+}
+
+int fa_fwd_schedule(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int N, int d,
+                    float scale, int causal, int dtype, int schedule, void* stream) {
+    return fwd_any(q, k, v, o, lse, B, H, H, N, d, scale, causal, dtype, schedule, stream);
 }
 
 int fa_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                float scale, int causal, int dtype, void* stream) {
-    return fwd_any(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, dtype, stream);
+    return fwd_any(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, dtype, FA_SCHED_AUTO, stream);
 }
 
 int fa_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,

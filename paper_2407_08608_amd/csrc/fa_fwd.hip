@@ -750,7 +750,19 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
 //     reads are software-pipelined eight MFMA steps ahead instead.
 template <typename Tag>
 static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
-                          int d, float scale, int causal, hipStream_t stream) {
+                          int d, float scale, int causal, int schedule, hipStream_t stream) {
+    if (schedule != FA_SCHED_AUTO) {
+        // forced kernel choice for the scheduling ablation (section 4.2's table, re-done on this chip)
+        if (d != 128) return FA_ERR_UNSUPPORTED;
+        switch (schedule) {
+            case FA_SCHED_LOCKSTEP_4W:
+                return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            case FA_SCHED_LOCKSTEP_8W:
+                return launch_16bit<Tag, 128, 128, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            case FA_SCHED_PINGPONG: return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            default: return FA_ERR_SHAPE;
+        }
+    }
     const bool small_tile = causal ? (N <= 2048) : (N <= 512);
     switch (d) {
         case 64:
@@ -765,13 +777,13 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
 }
 
 int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
-                    float scale, int causal, hipStream_t stream) {
-    return dispatch_16bit<bf16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, stream);
+                    float scale, int causal, int schedule, hipStream_t stream) {
+    return dispatch_16bit<bf16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, schedule, stream);
 }
 
 int launch_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
-                   float scale, int causal, hipStream_t stream) {
-    return dispatch_16bit<f16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, stream);
+                   float scale, int causal, int schedule, hipStream_t stream) {
+    return dispatch_16bit<f16_tag>(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, schedule, stream);
 }
 
 int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,

@@ -10,9 +10,9 @@
 namespace fa {
 
 int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
-                    float scale, int causal, hipStream_t stream);
+                    float scale, int causal, int schedule, hipStream_t stream);
 int launch_fwd_f16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
-                   float scale, int causal, hipStream_t stream);
+                   float scale, int causal, int schedule, hipStream_t stream);
 int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                    float scale, int causal, hipStream_t stream);
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,

@@ -123,3 +123,32 @@ def test_bf16_benchmark_shapes_sampled_rows(N, d, causal):
     assert e_o <= O_MAXABS and r_o <= O_RMSE and e_l <= L_MAXABS, (e_o, r_o, e_l)
     # property that holds at any size: nothing non-finite anywhere in the full output
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("schedule", [binding.FA_SCHED_LOCKSTEP_4W, binding.FA_SCHED_LOCKSTEP_8W,
+                                      binding.FA_SCHED_PINGPONG])
+@pytest.mark.parametrize("N", [1, 200, 777, 1300])
+def test_every_forced_schedule_matches_the_oracle(N, schedule, causal, dtype):
+    # the ablation entry point (section 4.2's experiment) must compute the same function whichever
+    # kernel it forces, including shapes the automatic choice would give to another kernel
+    q, k, v = inputs.qkv(90 + N, 2, 2, N, 128, dtype)
+    o, lse = binding.fa_fwd_schedule(q.cuda(), k.cuda(), v.cuda(), 128 ** -0.5, causal, schedule)
+    torch.cuda.synchronize()
+    o_ref, l_ref = oracle.attention_fwd(f64(q), f64(k), f64(v), 128 ** -0.5, causal)
+    e_o, r_o, e_l = max_abs(f64(o), o_ref), rmse(f64(o), o_ref), max_abs(f64(lse), l_ref)
+    assert e_o <= O_MAXABS and r_o <= O_RMSE and e_l <= L_MAXABS, (e_o, r_o, e_l)
+
+
+def test_forced_schedule_rejects_what_it_cannot_run():
+    q, k, v = (t.cuda() for t in inputs.qkv(95, 1, 1, 64, 64, "bf16"))
+    with pytest.raises(binding.FaError) as e:
+        binding.fa_fwd_schedule(q, k, v, 0.125, False, binding.FA_SCHED_PINGPONG)
+    assert e.value.status == 4
+    with pytest.raises(binding.FaError) as e:
+        binding.fa_fwd_schedule(q, k, v, 0.125, False, 7)
+    assert e.value.status == 2
+    o1, l1 = binding.fa_fwd_schedule(q, k, v, 0.125, False, binding.FA_SCHED_AUTO)
+    o2, l2 = binding.fa_fwd(q, k, v, 0.125, False)
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
