@@ -66,10 +66,14 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int wave = tid >> 6, lane = tid & 63;
     const int col = lane & 31, half = lane >> 5;
 
+    // Work items.  Non-causal: one query tile.  Causal: query tiles i and n_qtiles-1-i of a head,
+    // one after the other, so that every item covers the same number of key blocks (with an odd
+    // tile count the middle tile is an item of its own).
     int id = xcd_contiguous(blockIdx.x, total_wg);
-    const int bh = id / n_qtiles;
-    int qt = id % n_qtiles;
-    if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
 
     const size_t head_off = (size_t)bh * N * D;
     const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
@@ -77,8 +81,13 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const uint16_t* kh = k + kv_off;
     const uint16_t* vh = v + kv_off;
 
-    const int wave_q0 = qt * BR + wave * (32 * RQ);
     const float sc = scale * kLog2e;  // exp(scale*s - scale*m) = exp2(sc*s - sc*m)
+
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    // the longer tile first; every LDS read of the previous pass was followed by a barrier
+    const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
+    const int wave_q0 = qt * BR + wave * (32 * RQ);
 
     // Q_i^T as the B operand, resident in registers for the whole loop
     i32x4 qreg[RQ][KS];
@@ -305,6 +314,7 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
             if (half == 0) lse[(size_t)bh * N + qi] = (m_run[rq] * sc + log2f(l)) * kLn2;
         }
     }
+    }  // passes of a causal pair
 }
 
 // ---------------------------------------------------------------------------------------
@@ -365,37 +375,26 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const int group = wave >> 2;
     const int slab = (wave & 3) * 2 + group;
 
+    // Work items.  Non-causal: one query tile.  Causal: query tiles i and n_qtiles-1-i of a head,
+    // one after the other -- every item then covers the same number of key blocks, so the grid
+    // has no long and short workgroups and no tail of stragglers (with an odd tile count the
+    // middle tile is an item of its own).
     int id = xcd_contiguous(blockIdx.x, total_wg);
-    const int bh = id / n_qtiles;
-    int qt = id % n_qtiles;
-    if (CAUSAL) qt = n_qtiles - 1 - qt;  // longest rows first
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
 
     const size_t head_off = (size_t)bh * N * D;
     const uint16_t* qh = q + head_off;
-    const int wave_q0 = qt * BR + slab * 32;
+    int wave_q0 = 0;  // first query row of this wave in the current pass
     const float sc = scale * kLog2e;
     float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
     asm volatile("" : "+v"(sc_v));
 
     i32x4 qreg[KS];
-    {
-        int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-            qreg[ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
-    }
-
     f32x16 oacc[DT];
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
-
-    const int last_q = min(qt * BR + BR, N) - 1;
-    const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
-    // blocks 0 .. nb_w-1 concern this wave (all of them unless causal)
-    const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
 
     // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
     const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
@@ -563,6 +562,30 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const std::true_type yes{};
     const std::false_type no{};
 
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;  // the longer tile first
+    wave_q0 = qt * BR + slab * 32;
+    {
+        int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qreg[ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
+    }
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    m_run = -INFINITY;
+    l_run = 0.f;
+    const int last_q = min(qt * BR + BR, N) - 1;
+    const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+    // blocks 0 .. nb_w-1 concern this wave (all of them unless causal)
+    const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
+    // every wave's staging loads of the previous pass have landed (each waited for its own
+    // before its epilogue) and every LDS read of that pass is done
+    if (pass > 0) barrier();
+
     // ---- prologue: K(0), K(1), K(2), V(0), V(1) staged and visible before the first iteration
     stage(0, 0);
     stage(1, 1);
@@ -623,6 +646,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
             }
         if (half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
     }
+    }  // passes of a causal pair
 }
 
 // ---------------------------------------------------------------------------------------
@@ -703,7 +727,7 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
                         float scale, int causal, hipStream_t stream) {
     constexpr int BR = NW * 32 * RQ;
     int n_qtiles = (N + BR - 1) / BR;
-    long total = (long)B * H * n_qtiles;
+    long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     dim3 grid((unsigned)total), block(NW * 64);
     auto qp = static_cast<const uint16_t*>(q);
@@ -724,7 +748,7 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
                            float scale, int causal, hipStream_t stream) {
     constexpr int BR = 256, BC = 64, P = 4;
     int n_qtiles = (N + BR - 1) / BR;
-    long total = (long)B * H * n_qtiles;
+    long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     dim3 grid((unsigned)total), block(512);
     auto qp = static_cast<const uint16_t*>(q);
@@ -741,9 +765,9 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
 }
 
 // Kernel choice (measured on MI355X at the 16k-token benchmark shapes):
-//   d = 128: the eight-wave ping-pong kernel from 1024 keys on (causal: from 4096 on); shorter
-//     problems keep 128-row workgroups of four waves, which fill the chip better and leave fewer
-//     waves idle on the causal diagonal.
+//   d = 128: the eight-wave ping-pong kernel above 512 keys (causal tiles are paired into items
+//     of equal length there, so its coarser tiles cost no balance); shorter problems keep 128-row
+//     workgroups of four waves, which fill the chip better.
 //   d = 64: eight waves share each K/V block (256 query rows per workgroup, two waves per SIMD),
 //     four waves for short problems.
 //   d = 256: the 128-register output accumulator allows only one wave per SIMD, so the operand
@@ -769,7 +793,7 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
             if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 128:
-            if (small_tile) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            if (N <= 512) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
