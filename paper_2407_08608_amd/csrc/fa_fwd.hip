@@ -787,7 +787,7 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
             default: return FA_ERR_SHAPE;
         }
     }
-    const bool small_tile = causal ? (N <= 2048) : (N <= 512);
+    const bool small_tile = N <= 512;
     switch (d) {
         case 64:
             if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);

@@ -61,16 +61,24 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
     const int wave = tid >> 6, lane = tid & 63;
     const int col = lane & 31, half = lane >> 5;
 
+    // Work items.  Non-causal: one query tile.  Causal: query tiles i and n_qtiles-1-i of a head,
+    // one after the other, so that every item covers the same number of key blocks (with an odd
+    // tile count the middle tile is an item of its own).
     int id = xcd_contiguous(blockIdx.x, total_wg);
-    const int bh = id / n_qtiles;
-    int qt = id % n_qtiles;
-    if (CAUSAL) qt = n_qtiles - 1 - qt;
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
 
     const size_t head_off = (size_t)bh * N * D;
     const uint8_t* qh = q + head_off;
     const int kv_bh = bh / kv_group;  // grouped-query: kv_group query heads per K/V head
     const uint8_t* kh = k + (size_t)kv_bh * N * D;
     const uint8_t* vh = v + (size_t)kv_bh * N * D;
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    // the longer tile first; every LDS read of the previous pass was followed by a barrier
+    const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;
     const int wave_q0 = qt * BR + wave * 32;
 
     float sq = 1.0f;
@@ -257,6 +265,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
             }
         if (half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
     }
+    }  // passes of a causal pair
 }
 
 template <int D, int BC, int NW>
@@ -266,7 +275,7 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
     constexpr int BR = NW * 32;
     int n_qtiles = (N + BR - 1) / BR;
     int n_sblocks = (N + 127) / 128;
-    long total = (long)B * H * n_qtiles;
+    long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     dim3 grid((unsigned)total), block(NW * 64);
     auto qp = static_cast<const uint8_t*>(q8);
@@ -289,7 +298,7 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
                    const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d, float scale, int causal,
                    hipStream_t stream) {
-    const bool small_tile = causal ? (N <= 2048) : (N <= 512);
+    const bool small_tile = N <= 512;
     switch (d) {
         case 64:
             if (small_tile) return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
