@@ -350,7 +350,8 @@ template <typename Tag, int BC, int P, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2)
 fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
-                       int N, int n_qtiles, int total_wg, int kv_group, float scale) {
+                       int N, int n_qtiles, int total_wg, int total_items, int items_per_wg, int kv_group,
+                       float scale) {
     constexpr int D = 128;
     constexpr int BR = 256;
     constexpr int NS = 4;              // LDS stages per tensor
@@ -379,14 +380,16 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     // one after the other -- every item then covers the same number of key blocks, so the grid
     // has no long and short workgroups and no tail of stragglers (with an odd tile count the
     // middle tile is an item of its own).
-    int id = xcd_contiguous(blockIdx.x, total_wg);
-    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
-    const int bh = id / n_items;
-    const int item = id % n_items;
-    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
+    // A workgroup works through up to items_per_wg items, total_wg apart (the grid is sized to the
+    // chip, so that workgroup start-up is paid once per compute unit rather than once per tile;
+    // at any time the workgroups of an XCD are on neighbouring tiles of the same heads and share
+    // K and V in its L2).
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;  // per head
+    const int first_item = xcd_contiguous(blockIdx.x, total_wg);
+    (void)items_per_wg;
 
-    const size_t head_off = (size_t)bh * N * D;
-    const uint16_t* qh = q + head_off;
+    int bh = 0;
+    size_t head_off = 0;
     int wave_q0 = 0;  // first query row of this wave in the current pass
     const float sc = scale * kLog2e;
     float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
@@ -397,9 +400,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     float m_run = -INFINITY, l_run = 0.f;
 
     // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
-    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
-    const BufferWords k_rsrc = make_buffer_words(k + kv_off, (uint32_t)N * D * 2);
-    const BufferWords v_rsrc = make_buffer_words(v + kv_off, (uint32_t)N * D * 2);
+    BufferWords k_rsrc, v_rsrc;  // K and V of the current item's head
     const int st_row = 4 * wave + (lane >> 4), st_pos = lane & 15;
     const int k_src = st_row * ROWB + ((st_pos ^ (st_row & 15)) << 4);        // byte offset within a tile
     const int v_src = st_row * ROWB + ((st_pos ^ ((st_row & 3) << 2)) << 4);
@@ -563,6 +564,16 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const std::false_type no{};
 
 #pragma nounroll
+    for (int it = first_item; it < total_items; it += total_wg) {
+    bh = it / n_items;
+    const int item = it % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
+    head_off = (size_t)bh * N * D;
+    const uint16_t* qh = q + head_off;
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
+    k_rsrc = make_buffer_words(k + kv_off, (uint32_t)N * D * 2);
+    v_rsrc = make_buffer_words(v + kv_off, (uint32_t)N * D * 2);
+#pragma nounroll
     for (int pass = 0; pass < n_pass; ++pass) {
     const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;  // the longer tile first
     wave_q0 = qt * BR + slab * 32;
@@ -584,7 +595,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
     // every wave's staging loads of the previous pass have landed (each waited for its own
     // before its epilogue) and every LDS read of that pass is done
-    if (pass > 0) barrier();
+    if (pass > 0 || it > first_item) barrier();
 
     // ---- prologue: K(0), K(1), K(2), V(0), V(1) staged and visible before the first iteration
     stage(0, 0);
@@ -647,6 +658,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
         if (half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
     }
     }  // passes of a causal pair
+    }  // items of this workgroup
 }
 
 // ---------------------------------------------------------------------------------------
@@ -743,6 +755,9 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
+constexpr int kComputeUnits = 256;
+constexpr int kMaxItemsPerWg = 4;
+
 template <typename Tag>
 static int launch_pingpong(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                            float scale, int causal, hipStream_t stream) {
@@ -750,17 +765,21 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
     int n_qtiles = (N + BR - 1) / BR;
     long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
-    dim3 grid((unsigned)total), block(512);
+    // one workgroup fits a compute unit: give each of the 256 an equal run of consecutive items
+    int per_wg = (int)((total + kComputeUnits - 1) / kComputeUnits);
+    if (per_wg > kMaxItemsPerWg) per_wg = kMaxItemsPerWg;
+    const int n_wg = (int)((total + per_wg - 1) / per_wg);
+    dim3 grid((unsigned)n_wg), block(512);
     auto qp = static_cast<const uint16_t*>(q);
     auto kp = static_cast<const uint16_t*>(k);
     auto vp = static_cast<const uint16_t*>(v);
     auto op = static_cast<uint16_t*>(o);
     if (causal)
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, (int)total, H / H_kv, scale);
+                           n_qtiles, n_wg, (int)total, per_wg, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, (int)total, H / H_kv, scale);
+                           n_qtiles, n_wg, (int)total, per_wg, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
