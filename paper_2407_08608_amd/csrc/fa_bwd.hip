@@ -487,18 +487,12 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         __syncthreads();
     }
 
-    if (qi < N) {
-        uint16_t* row = dq + head_off + (size_t)qi * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                i32x2 w;
-                w[0] = E::pack2(acc[dt][4 * g] * scale, acc[dt][4 * g + 1] * scale);
-                w[1] = E::pack2(acc[dt][4 * g + 2] * scale, acc[dt][4 * g + 3] * scale);
-                *reinterpret_cast<i32x2*>(row + dt * 32 + 8 * g + 4 * half) = w;
-            }
-    }
+    // dQ_i = scale * acc.  Every LDS read of the loop was followed by a barrier, so the K and V
+    // buffers are free: each wave takes 4 KiB of them to transpose its tile into whole 128-byte lines.
+    static_assert(NW <= 8 && sizeof(lds_k) >= 4 * 4096 && sizeof(lds_v) >= 4 * 4096, "patches must fit");
+    char* patch = (wave < 4 ? reinterpret_cast<char*>(&lds_k[0][0]) : reinterpret_cast<char*>(&lds_v[0][0])) +
+                  (wave & 3) * 4096;
+    store_rows_via_lds<Tag, DT>(acc, scale, patch, make_buffer(dq + head_off, (uint32_t)N * D * 2), wave_q0, lane);
 }
 
 // ---------------------------------------------------------------------------------------

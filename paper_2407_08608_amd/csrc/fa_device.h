@@ -139,6 +139,41 @@ static __device__ __forceinline__ void global_to_lds_16B(const BufferWords& rsrc
 
 static __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Stores a wave's 32-row x (32 DT)-column fp32 accumulator tile (MFMA result layout with rows as
+// lane columns: lane (col, half) holds row `col`; register r of tile dt is column
+// 32 dt + 8 (r / 4) + 4 half + r % 4) as 16-bit elements, scaled by `factor`.  Stored straight from
+// that layout every store instruction would touch 32 rows with 16 bytes each; instead the tile
+// goes through `patch` (4 KiB of LDS private to the wave), 128 bytes of every row at a time, and
+// leaves as whole 128-byte lines: 16-byte chunk c of row r sits at chunk c ^ (r % 8) of the patch.
+// `rsrc` covers the [rows][32 DT] destination; rows at or past its end are dropped by the hardware.
+template <typename Tag, int DT>
+static __device__ __forceinline__ void store_rows_via_lds(const f32x16 (&acc)[DT], float factor, char* patch,
+                                                           __amdgpu_buffer_rsrc_t rsrc, int row0, int lane) {
+    static_assert(DT % 2 == 0, "128 bytes of a row are two 32-column tiles");
+    using E = Elem<Tag>;
+    constexpr int ROWB = DT * 64;  // bytes per destination row
+    const int col = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int hd = 0; hd < DT / 2; ++hd) {
+#pragma unroll
+        for (int d2 = 0; d2 < 2; ++d2)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int dt = 2 * hd + d2;
+                i32x2 w;
+                w[0] = E::pack2(acc[dt][4 * g] * factor, acc[dt][4 * g + 1] * factor);
+                w[1] = E::pack2(acc[dt][4 * g + 2] * factor, acc[dt][4 * g + 3] * factor);
+                *reinterpret_cast<i32x2*>(patch + col * 128 + (((4 * d2 + g) ^ (col & 7)) << 4) + 8 * half) = w;
+            }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = 8 * i + (lane >> 3), pc = lane & 7;
+            const i32x4 w = *reinterpret_cast<const i32x4*>(patch + r * 128 + (pc << 4));
+            __builtin_amdgcn_raw_buffer_store_b128(w, rsrc, (row0 + r) * ROWB + hd * 128 + ((pc ^ (r & 7)) << 4), 0, 0);
+        }
+    }
+}
+
 // The chip deals consecutive workgroup ids round-robin to its 8 XCDs, each with a private
 // L2.  Remap a linear id so that ids landing on one XCD cover a contiguous range of work
 // items (all query tiles of a head share that head's K and V in one L2).

@@ -44,7 +44,8 @@ struct TileCopy {
 };
 
 template <typename Tag, int D, int BC, int NW, int RQ, int PD, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64, (RQ == 1 && D <= 128) ? 2 : 1)
+// (the second launch bound is waves per SIMD: two eight-wave workgroups of the d = 64 kernel share a CU)
+__global__ void __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : (RQ == 1 && D <= 128) ? 2 : 1)
 fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
                     int N, int n_qtiles, int total_wg, int kv_group, float scale) {
@@ -294,26 +295,20 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         __syncthreads();
     }
 
-    // ---- epilogue: O / l, L = m + log l
-#pragma unroll
-    for (int rq = 0; rq < RQ; ++rq) {
-        int qi = wave_q0 + rq * 32 + col;
-        float l = sum_both_halves(l_run[rq]);
-        float inv = 1.0f / l;
-        if (qi < N) {
-            uint16_t* orow = o + head_off + (size_t)qi * D;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    i32x2 w;
-                    w[0] = E::pack2(oacc[rq][dt][4 * g] * inv, oacc[rq][dt][4 * g + 1] * inv);
-                    w[1] = E::pack2(oacc[rq][dt][4 * g + 2] * inv, oacc[rq][dt][4 * g + 3] * inv);
-                    *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
-                }
-            if (half == 0) lse[(size_t)bh * N + qi] = (m_run[rq] * sc + log2f(l)) * kLn2;
-        }
+    // ---- epilogue: O / l, L = m + log l.  Every LDS read of the loop was followed by a barrier,
+    // so the K and V buffers are free: each wave takes 4 KiB of them to transpose its output tile.
+    static_assert(RQ == 1, "one 32-row slab per wave");
+    {
+        char* patch = (wave < 4 ? reinterpret_cast<char*>(&lds_k[0][0]) : reinterpret_cast<char*>(&lds_v[0][0])) +
+                      (wave & 3) * 4096;
+        static_assert(sizeof(lds_k) >= 4 * 4096 && sizeof(lds_v) >= 4 * 4096, "patches must fit");
+        const int qi = wave_q0 + col;
+        const float l = sum_both_halves(l_run[0]);
+        store_rows_via_lds<Tag, DT>(oacc[0], 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2), wave_q0,
+                                    lane);
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run[0] * sc + log2f(l)) * kLn2;
     }
+    if (pass + 1 < n_pass) __syncthreads();  // the next pass's first tile overwrites the patches
     }  // passes of a causal pair
 }
 
@@ -350,8 +345,7 @@ template <typename Tag, int BC, int P, bool CAUSAL>
 __global__ void __launch_bounds__(512, 2)
 fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
-                       int N, int n_qtiles, int total_wg, int total_items, int items_per_wg, int kv_group,
-                       float scale) {
+                       int N, int n_qtiles, int total_wg, int kv_group, float scale) {
     constexpr int D = 128;
     constexpr int BR = 256;
     constexpr int NS = 4;              // LDS stages per tensor
@@ -368,6 +362,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
 
     __shared__ __attribute__((aligned(1024))) char lds_k[NS * TILE];
     __shared__ __attribute__((aligned(1024))) char lds_v[NS * TILE];
+    __shared__ __attribute__((aligned(1024))) char lds_o[8 * 4096];  // output transposition, 4 KiB per wave
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -380,16 +375,14 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     // one after the other -- every item then covers the same number of key blocks, so the grid
     // has no long and short workgroups and no tail of stragglers (with an odd tile count the
     // middle tile is an item of its own).
-    // A workgroup works through up to items_per_wg items, total_wg apart (the grid is sized to the
-    // chip, so that workgroup start-up is paid once per compute unit rather than once per tile;
-    // at any time the workgroups of an XCD are on neighbouring tiles of the same heads and share
-    // K and V in its L2).
-    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;  // per head
-    const int first_item = xcd_contiguous(blockIdx.x, total_wg);
-    (void)items_per_wg;
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
 
-    int bh = 0;
-    size_t head_off = 0;
+    const size_t head_off = (size_t)bh * N * D;
+    const uint16_t* qh = q + head_off;
     int wave_q0 = 0;  // first query row of this wave in the current pass
     const float sc = scale * kLog2e;
     float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
@@ -400,7 +393,9 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     float m_run = -INFINITY, l_run = 0.f;
 
     // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
-    BufferWords k_rsrc, v_rsrc;  // K and V of the current item's head
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
+    const BufferWords k_rsrc = make_buffer_words(k + kv_off, (uint32_t)N * D * 2);
+    const BufferWords v_rsrc = make_buffer_words(v + kv_off, (uint32_t)N * D * 2);
     const int st_row = 4 * wave + (lane >> 4), st_pos = lane & 15;
     const int k_src = st_row * ROWB + ((st_pos ^ (st_row & 15)) << 4);        // byte offset within a tile
     const int v_src = st_row * ROWB + ((st_pos ^ ((st_row & 3) << 2)) << 4);
@@ -564,16 +559,6 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const std::false_type no{};
 
 #pragma nounroll
-    for (int it = first_item; it < total_items; it += total_wg) {
-    bh = it / n_items;
-    const int item = it % n_items;
-    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
-    head_off = (size_t)bh * N * D;
-    const uint16_t* qh = q + head_off;
-    const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
-    k_rsrc = make_buffer_words(k + kv_off, (uint32_t)N * D * 2);
-    v_rsrc = make_buffer_words(v + kv_off, (uint32_t)N * D * 2);
-#pragma nounroll
     for (int pass = 0; pass < n_pass; ++pass) {
     const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;  // the longer tile first
     wave_q0 = qt * BR + slab * 32;
@@ -595,7 +580,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     const int nb_w = CAUSAL ? min(n_blocks, (wave_q0 + 31) / BC + 1) : n_blocks;
     // every wave's staging loads of the previous pass have landed (each waited for its own
     // before its epilogue) and every LDS read of that pass is done
-    if (pass > 0 || it > first_item) barrier();
+    if (pass > 0) barrier();
 
     // ---- prologue: K(0), K(1), K(2), V(0), V(1) staged and visible before the first iteration
     stage(0, 0);
@@ -641,24 +626,14 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // staging loads past the last block: nothing may land after the end
 
     // ---- epilogue: O / l, L = m + log l
-    const int qi = wave_q0 + col;
-    const float l = sum_both_halves(l_run);
-    const float inv = 1.0f / l;
-    if (qi < N) {
-        uint16_t* orow = o + head_off + (size_t)qi * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                i32x2 w;
-                w[0] = E::pack2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
-                w[1] = E::pack2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
-                *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
-            }
-        if (half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
+    {
+        const int qi = wave_q0 + col;
+        const float l = sum_both_halves(l_run);
+        store_rows_via_lds<Tag, DT>(oacc, 1.0f / l, lds_o + wave * 4096, make_buffer(o + head_off, (uint32_t)N * D * 2),
+                                    wave_q0, lane);
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
     }
     }  // passes of a causal pair
-    }  // items of this workgroup
 }
 
 // ---------------------------------------------------------------------------------------
@@ -755,9 +730,6 @@ static int launch_16bit(const void* q, const void* k, const void* v, void* o, fl
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
-constexpr int kComputeUnits = 256;
-constexpr int kMaxItemsPerWg = 4;
-
 template <typename Tag>
 static int launch_pingpong(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                            float scale, int causal, hipStream_t stream) {
@@ -765,21 +737,17 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
     int n_qtiles = (N + BR - 1) / BR;
     long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
-    // one workgroup fits a compute unit: give each of the 256 an equal run of consecutive items
-    int per_wg = (int)((total + kComputeUnits - 1) / kComputeUnits);
-    if (per_wg > kMaxItemsPerWg) per_wg = kMaxItemsPerWg;
-    const int n_wg = (int)((total + per_wg - 1) / per_wg);
-    dim3 grid((unsigned)n_wg), block(512);
+    dim3 grid((unsigned)total), block(512);
     auto qp = static_cast<const uint16_t*>(q);
     auto kp = static_cast<const uint16_t*>(k);
     auto vp = static_cast<const uint16_t*>(v);
     auto op = static_cast<uint16_t*>(o);
     if (causal)
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, n_wg, (int)total, per_wg, H / H_kv, scale);
+                           n_qtiles, (int)total, H / H_kv, scale);
     else
         hipLaunchKernelGGL((fa_fwd_pingpong_kernel<Tag, BC, P, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N,
-                           n_qtiles, n_wg, (int)total, per_wg, H / H_kv, scale);
+                           n_qtiles, (int)total, H / H_kv, scale);
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 

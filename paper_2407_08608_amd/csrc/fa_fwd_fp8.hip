@@ -56,6 +56,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 
     __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][BC * KSTR];
     __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][BC * VSTR];
+    __shared__ __attribute__((aligned(128))) char lds_o[NW * 4096];  // output transposition, 4 KiB per wave
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -249,21 +250,14 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         __syncthreads();
     }
 
-    int qi = wave_q0 + col;
-    float l = sum_both_halves(l_run);
-    float inv = sv_cur / l;
-    if (qi < N) {
-        uint16_t* orow = o + head_off + (size_t)qi * D;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                i32x2 w;
-                w[0] = Elem<bf16_tag>::pack2(oacc[dt][4 * g] * inv, oacc[dt][4 * g + 1] * inv);
-                w[1] = Elem<bf16_tag>::pack2(oacc[dt][4 * g + 2] * inv, oacc[dt][4 * g + 3] * inv);
-                *reinterpret_cast<i32x2*>(orow + dt * 32 + 8 * g + 4 * half) = w;
-            }
-        if (half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
+    // ---- epilogue: O * s_V / l as bf16 (transposed through a wave-private LDS patch), L
+    {
+        char* patch = lds_o + wave * 4096;
+        const int qi = wave_q0 + col;
+        const float l = sum_both_halves(l_run);
+        store_rows_via_lds<bf16_tag, DT>(oacc, sv_cur / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
+                                         wave_q0, lane);
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
     }
     }  // passes of a causal pair
 }
