@@ -152,3 +152,21 @@ def test_forced_schedule_rejects_what_it_cannot_run():
     o1, l1 = binding.fa_fwd_schedule(q, k, v, 0.125, False, binding.FA_SCHED_AUTO)
     o2, l2 = binding.fa_fwd(q, k, v, 0.125, False)
     assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_calls_follow_the_current_stream_and_reuse_caller_buffers():
+    # the binding passes torch's current stream: work queued on a side stream must be ordered after
+    # that stream's earlier work (the fill below) and give the same bits as a default-stream call
+    q, k, v = (t.cuda() for t in inputs.qkv(96, 2, 4, 1500, 128, "bf16"))
+    o_ref, l_ref = binding.fa_fwd(q, k, v, 128 ** -0.5, True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    o = torch.empty_like(q)
+    lse = torch.empty_like(l_ref)
+    with torch.cuda.stream(side):
+        o.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        o2, l2 = binding.fa_fwd(q, k, v, 128 ** -0.5, True, o=o, lse=lse)
+    side.synchronize()
+    assert o2.data_ptr() == o.data_ptr() and l2.data_ptr() == lse.data_ptr()
+    assert torch.equal(o, o_ref) and torch.equal(lse, l_ref)
