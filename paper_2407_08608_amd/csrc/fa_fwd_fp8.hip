@@ -4,7 +4,7 @@
 // contract 64 elements per instruction and a lane holds 32 bytes of an operand.
 //   * Block quantisation: a block of S is rescaled by s_Q[i] * s_K[j], folded into the exp2
 //     multiplier, so it costs nothing per element.  The output accumulator is kept in units
-//     of the current V block's scale and converted when the block changes.
+//     of a reference V scale; a block's own scale enters through the exponent of P~.
 //   * Layout conformance: V is stored d-contiguous but must be contracted over keys.  The
 //     transposing LDS read (ds_read_b64_tr_b8) hands a lane 8 consecutive keys of one column,
 //     while the fp32 accumulator of S^T gives a lane-half alternating groups of 4 rows.  The
@@ -104,7 +104,9 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;  // m in log2 units of the real (scaled) scores
-    float sv_cur = 1.0f;
+    // reference V scale (see the softmax below); starts at the first block's
+    float sv_ref = 1.0f;
+    if constexpr (SCALED) sv_ref = v_scale[(size_t)kv_bh * n_sblocks];
 
     int last_q = min(qt * BR + BR, N) - 1;
     int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
@@ -184,38 +186,51 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     }
             }
 
-            // ---- online softmax in log2 units of the real scores
-            float mx = sacc[0][0];
+            // ---- online softmax in log2 units of the real scores.  Independent chains for the maximum
+            // and the sum: a wave gets few issue slots while its SIMD sibling streams MFMAs, and one
+            // long dependent chain would turn every slot missed into a stall.
+            float mxp[4] = {sacc[0][0], sacc[0][1], sacc[0][2], sacc[0][3]};
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[kt][r]);
-            mx = max_both_halves(mx) * sc;
+                for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
+            const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * sc;
             const bool raise = mx - m_run > kLazyLog2;
-            const bool new_vscale = sv_new != sv_cur;
-            if (__builtin_amdgcn_ballot_w64(raise) != 0 || new_vscale) {
-                // rescale for a raised reference maximum and / or a new V block scale (the
-                // accumulator is kept in units of the current V block's scale)
-                float corr = raise ? fast_exp2(m_run - mx) : 1.0f;
+            // V block scales: the accumulator is kept in units of a reference scale sv_ref, and a block
+            // whose scale is sv enters as P~ * (sv / sv_ref) -- a term in the exponent, no work per
+            // element.  sv_ref moves (and the accumulator is rescaled) only when that ratio leaves
+            // [1/16, 1.75]: above, P~ <= 256 would pass e4m3's 448; far below, P~ would sink into the
+            // subnormals.
+            float ratio = 1.0f;
+            if constexpr (SCALED) ratio = sv_new * __builtin_amdgcn_rcpf(sv_ref);
+            const bool move_ref = ratio > 1.75f || ratio < 0.0625f;
+            if (__builtin_amdgcn_ballot_w64(raise) != 0 || move_ref) {
+                float f = raise ? fast_exp2(m_run - mx) : 1.0f;
                 m_run = raise ? mx : m_run;
-                l_run *= corr;
-                float f = corr * (sv_cur / sv_new);
-                sv_cur = sv_new;
+                l_run *= f;
+                if (move_ref) {
+                    f *= sv_ref / sv_new;
+                    sv_ref = sv_new;
+                    ratio = 1.0f;
+                }
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
             }
-            const float mb = m_run - kPBias;
-            float psum = 0.f;
+            float mb = m_run - kPBias;
+            if constexpr (SCALED) mb -= __builtin_amdgcn_logf(ratio);  // log2
+            float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
+            asm volatile("" : "+v"(sc_v));
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};
             i32x8 pb[SL];
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
                 float p[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    p[r] = fast_exp2(__builtin_fmaf(sacc[kt][r], sc, -mb));
-                    psum += p[r];
+                    p[r] = fast_exp2(__builtin_fmaf(sacc[kt][r], sc_v, -mb));
+                    ps[r & 3] += p[r];
                 }
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
@@ -225,6 +240,9 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     pb[kt >> 1][4 * (kt & 1) + w] = word;
                 }
             }
+            // the row sum counts the unscaled P~
+            float psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            if constexpr (SCALED) psum *= __builtin_amdgcn_rcpf(ratio);
             l_run += psum;
 
             // ---- GEMM1: O^T += V_j^T P^T
@@ -255,7 +273,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         char* patch = lds_o + wave * 4096;
         const int qi = wave_q0 + col;
         const float l = sum_both_halves(l_run);
-        store_rows_via_lds<bf16_tag, DT>(oacc, sv_cur / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
+        store_rows_via_lds<bf16_tag, DT>(oacc, sv_ref / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
                                          wave_q0, lane);
         if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
     }

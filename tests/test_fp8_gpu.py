@@ -130,6 +130,29 @@ def test_fp8_forward_block_scales_really_differ_per_block():
         assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_fp8_forward_v_scales_jump_up_and_down_by_large_factors(causal):
+    # the kernel keeps its accumulator in units of a reference V scale that it moves only on large
+    # jumps: make consecutive V blocks differ by factors far outside and inside that band, with an
+    # all-zero block (scale 1 by convention) in the middle
+    B, H, N, d = 1, 2, 1024, 128
+    q, k, v = inputs.qkv(42, B, H, N, d, "bf16")
+    for t, f in enumerate([1.0, 64.0, 0.02, 0.0, 3.0, 1.5, 0.001, 200.0]):
+        v[:, :, t * 128:(t + 1) * 128] *= f
+    codes, scales = zip(*[f8.quantize(x.float().numpy(), None, 128) for x in (q, k, v)])
+    assert scales[2][0, 0, 3] == 1.0 and scales[2][0, 0, 1] > 30 * scales[2][0, 0, 0]
+    o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, causal)
+    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
+    o_ref, l_ref = oracle.attention_fwd(*deq, d ** -0.5, causal)
+    assert np.isfinite(f64(o)).all()
+    assert max_abs(f64(lse), l_ref) <= 2e-3
+    # per row: P~ rounding is 2^-4 relative on every term, so the error is bounded by 2^-4 of the
+    # P-weighted mean of |V^| over the keys the row sees (plus the bf16 store)
+    p_abs, _ = oracle.attention_fwd(deq[0], deq[1], np.abs(deq[2]), d ** -0.5, causal)
+    err = np.abs(f64(o) - o_ref)
+    assert (err <= 2.0 ** -4 * 1.05 * p_abs + 2.0 ** -8 * np.abs(o_ref) + 1e-6).all()
+
+
 def test_fp8_unit_scale_entry_point_and_constant_values():
     B, H, N, d = 1, 2, 200, 128
     rng = np.random.default_rng(41)
