@@ -24,8 +24,8 @@ PEAK_FP8_TFLOPS = 5000.0
 # HBM bytes per launch of the dominant kernel (the ping-pong non-causal d=128 kernel, which serves
 # seqlen 1k..16k: average over those five shapes), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/fa_fwd_bf16_d128_hbm_traffic.txt (copy-kernel calibration factors 2.000
-# and 1.000): four shapes move 257.5 MiB, seqlen 16k moves 385 MiB.  Algorithmic: 2.695e8 bytes.
-TRAFFIC_BYTES_PER_LAUNCH = 2.969e8
+# and 1.000): four shapes move 257.3 MiB, seqlen 16k moves 385 MiB.  Algorithmic: 2.695e8 bytes.
+TRAFFIC_BYTES_PER_LAUNCH = 2.967e8
 DOMINANT_MIN_SEQLEN = 1024  # the launcher uses the 4-wave tile below this (non-causal)
 
 
