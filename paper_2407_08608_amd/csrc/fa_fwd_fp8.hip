@@ -3,8 +3,8 @@
 // Same tiling as the 16-bit kernel (Algorithm 1), on v_mfma_f32_32x32x64_f8f6f4: both GEMMs
 // contract 64 elements per instruction and a lane holds 32 bytes of an operand.
 //   * Block quantisation: a block of S is rescaled by s_Q[i] * s_K[j], folded into the exp2
-//     multiplier, so it costs nothing per element.  The output accumulator is kept in units
-//     of a reference V scale; a block's own scale enters through the exponent of P~.
+//     multiplier, so it costs nothing per element.  A V block's scale enters as an offset in
+//     the exponent of P~ (the numerator's weights are p * s_V), which costs nothing either.
 //   * Layout conformance: V is stored d-contiguous but must be contracted over keys.  The
 //     transposing LDS read (ds_read_b64_tr_b8) hands a lane 8 consecutive keys of one column,
 //     while the fp32 accumulator of S^T gives a lane-half alternating groups of 4 rows.  The
@@ -103,10 +103,8 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;  // m in log2 units of the real (scaled) scores
-    // reference V scale (see the softmax below); starts at the first block's
-    float sv_ref = 1.0f;
-    if constexpr (SCALED) sv_ref = v_scale[(size_t)kv_bh * n_sblocks];
+    // m: running (lazily raised) maximum, in log2 units, of the real scores plus log2 of their V block's scale
+    float m_run = -INFINITY, l_run = 0.f;
 
     int last_q = min(qt * BR + BR, N) - 1;
     int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
@@ -194,32 +192,25 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
-            const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * sc;
+            // V block scales: O = sum_k p_k s_V[j] V^_k / sum_k p_k.  The numerator's weights are
+            // 2^(s_k + log2 s_V[j]), so the block's scale is an offset in the exponent of P~ -- no work
+            // per element -- and the running maximum is taken over the offset scores: P~ <= 2^(7+1) for
+            // every block, and the key that raises the maximum gets P~ = 2^7 exactly.  The row sum needs
+            // the weights without the offset: the block's sum divided by s_V[j], once per block.
+            float lsv = 0.f;
+            if constexpr (SCALED) lsv = __builtin_amdgcn_logf(sv_new);  // log2
+            const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * sc + lsv;
             const bool raise = mx - m_run > kLazyLog2;
-            // V block scales: the accumulator is kept in units of a reference scale sv_ref, and a block
-            // whose scale is sv enters as P~ * (sv / sv_ref) -- a term in the exponent, no work per
-            // element.  sv_ref moves (and the accumulator is rescaled) only when that ratio leaves
-            // [1/16, 1.75]: above, P~ <= 256 would pass e4m3's 448; far below, P~ would sink into the
-            // subnormals.
-            float ratio = 1.0f;
-            if constexpr (SCALED) ratio = sv_new * __builtin_amdgcn_rcpf(sv_ref);
-            const bool move_ref = ratio > 1.75f || ratio < 0.0625f;
-            if (__builtin_amdgcn_ballot_w64(raise) != 0 || move_ref) {
-                float f = raise ? fast_exp2(m_run - mx) : 1.0f;
+            if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                const float f = raise ? fast_exp2(m_run - mx) : 1.0f;
                 m_run = raise ? mx : m_run;
                 l_run *= f;
-                if (move_ref) {
-                    f *= sv_ref / sv_new;
-                    sv_ref = sv_new;
-                    ratio = 1.0f;
-                }
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
             }
-            float mb = m_run - kPBias;
-            if constexpr (SCALED) mb -= __builtin_amdgcn_logf(ratio);  // log2
+            const float mb = m_run - kPBias - lsv;
             float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
             asm volatile("" : "+v"(sc_v));
             float ps[4] = {0.f, 0.f, 0.f, 0.f};
@@ -240,9 +231,8 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     pb[kt >> 1][4 * (kt & 1) + w] = word;
                 }
             }
-            // the row sum counts the unscaled P~
             float psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
-            if constexpr (SCALED) psum *= __builtin_amdgcn_rcpf(ratio);
+            if constexpr (SCALED) psum *= __builtin_amdgcn_rcpf(sv_new);
             l_run += psum;
 
             // ---- GEMM1: O^T += V_j^T P^T
@@ -273,7 +263,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         char* patch = lds_o + wave * 4096;
         const int qi = wave_q0 + col;
         const float l = sum_both_halves(l_run);
-        store_rows_via_lds<bf16_tag, DT>(oacc, sv_ref / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
+        store_rows_via_lds<bf16_tag, DT>(oacc, 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
                                          wave_q0, lane);
         if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
     }
