@@ -13,16 +13,16 @@
 //     accumulator registers to operand registers with conversions only, no cross-lane moves.
 //     This is the same idea as the paper's register permutation plus matching V-row
 //     permutation, rederived for the gfx950 layouts.
-//   * P~ = exp2(s - m_ref + 7) where the reference maximum m_ref is raised only when a block's
-//     maximum exceeds it by more than 1 (log2 units), so P~ <= 256 < 448: the bias uses more of
+//   * P~ = exp2(s - m_ref + 6) where the reference maximum m_ref is raised only when a block's
+//     maximum exceeds it by more than 2 (log2 units), so P~ <= 256 < 448: the bias uses more of
 //     e4m3's range, both factors cancel in O / l, and L subtracts the bias again.
 #include "fa_device.h"
 #include "fa_launch.h"
 
 namespace fa {
 
-constexpr float kPBias = 7.0f;
-constexpr float kLazyLog2 = 1.0f;
+constexpr float kPBias = 6.0f;
+constexpr float kLazyLog2 = 2.0f;
 
 static __device__ __forceinline__ f32x16 mma_fp8(i32x8 a, i32x8 b, f32x16 c) {
     // cbsz = blgp = 0: both operands e4m3; scale exponents 127 = 1.0
@@ -194,8 +194,8 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                 for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
             // V block scales: O = sum_k p_k s_V[j] V^_k / sum_k p_k.  The numerator's weights are
             // 2^(s_k + log2 s_V[j]), so the block's scale is an offset in the exponent of P~ -- no work
-            // per element -- and the running maximum is taken over the offset scores: P~ <= 2^(7+1) for
-            // every block, and the key that raises the maximum gets P~ = 2^7 exactly.  The row sum needs
+            // per element -- and the running maximum is taken over the offset scores: P~ <= 2^(6+2) for
+            // every block, and the key that raises the maximum gets P~ = 2^6 exactly.  The row sum needs
             // the weights without the offset: the block's sum divided by s_V[j], once per block.
             float lsv = 0.f;
             if constexpr (SCALED) lsv = __builtin_amdgcn_logf(sv_new);  // log2
