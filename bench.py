@@ -223,7 +223,7 @@ def extra_table(torch, binding, inputs, dev):
     # FP8: pre-pass (HBM-bound) and forward.  Speed rows use N(0,1) inputs like the 16-bit rows; one more
     # row per head dimension uses the heavy-tailed inputs of the paper's error study (section 4.3), on which
     # the running maximum is raised -- and the accumulator rescaled -- far more often.
-    for d, N, heavy in [(d, N, False) for d in (128, 256) for N in (512, 4096, 16384)] + [(128, 16384, True),
+    for d, N, heavy in [(d, N, False) for d in (64, 128, 256) for N in (512, 4096, 16384)] + [(128, 16384, True),
                                                                                            (256, 16384, True)]:
         B, H = inputs.benchmark_shape(N, d)
         q, k, v = (t.to(dev) for t in inputs.qkv(7, B, H, N, d, "bf16", heavy_tailed=heavy))
