@@ -252,7 +252,7 @@ def extra_table(torch, binding, inputs, dev):
                         ("lockstep_4_waves_2_workgroups", binding.FA_SCHED_LOCKSTEP_4W)):
         ms = _time_call(torch, lambda: binding.fa_fwd_schedule(q, k, v, d ** -0.5, False, sched, o=o, lse=lse))
         table[f"ablation_f16_b4_s8448_h16_d128_{name}"] = {"ms": round(ms, 4), "tflops": tf(B, H, N, d, False, ms)}
-    for d, N in ((128, 1024), (128, 4096), (128, 16384), (64, 4096), (64, 16384)):  # bf16 backward
+    for d, N in ((128, 1024), (128, 4096), (128, 16384), (64, 4096), (64, 16384), (256, 4096), (256, 16384)):  # bf16 backward
         B, H = inputs.benchmark_shape(N, d)
         q, k, v, do = (torch.randn((B, H, N, d), device=dev, dtype=torch.bfloat16) for _ in range(4))
         ws = torch.empty(binding.fa_bwd_workspace_bytes(B, H, N, d), device=dev, dtype=torch.uint8)

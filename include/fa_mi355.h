@@ -110,8 +110,8 @@ int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales,
  *   dq, dk, dv       : [B,H,N,d] of `dtype`                                   (device, written)
  *   workspace        : device scratch of at least fa_bwd_workspace_bytes(...) bytes (it holds D),
  *                      16-byte aligned, owned by the caller, contents undefined on return.
- * dtype FA_BF16 or FA_F16; d = 64 or 128 (others: FA_ERR_UNSUPPORTED; fa_bwd_workspace_bytes
- * then returns 0).  Nothing is accumulated
+ * dtype FA_BF16 or FA_F16 (others: FA_ERR_UNSUPPORTED; fa_bwd_workspace_bytes then returns 0);
+ * d = 64, 128 or 256.  Nothing is accumulated
  * with atomics: results are bit-for-bit repeatable.
  */
 size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype);

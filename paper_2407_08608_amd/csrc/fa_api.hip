@@ -116,7 +116,7 @@ int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales, 
 }
 
 size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype) {
-    if (B <= 0 || H <= 0 || N <= 0 || (d != 64 && d != 128)) return 0;
+    if (B <= 0 || H <= 0 || N <= 0 || !head_dim_ok(d)) return 0;
     if (dtype != FA_BF16 && dtype != FA_F16) return 0;
     return fa::bwd_workspace_bytes(B, H, N, d);
 }
@@ -129,7 +129,7 @@ static int bwd_any(const void* q, const void* k, const void* v, const void* o, c
     int st = check_common(B, H, N, d, scale, causal);
     if (st != FA_OK) return st;
     if (H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
-    if ((d != 64 && d != 128) || (dtype != FA_BF16 && dtype != FA_F16)) return FA_ERR_UNSUPPORTED;
+    if (dtype != FA_BF16 && dtype != FA_F16) return FA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dout) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
         return FA_ERR_ALIGN;

@@ -32,7 +32,7 @@ constexpr int kPipe = 2;  // MFMA steps by which LDS operand reads lead their us
 // LDS row stride (elements) of tiles that are read both by rows and transposed: an odd multiple
 // of 16 bytes keeps the row reads conflict-free, and the offset from a multiple of 256 bytes
 // decides how much the four rows of a transposing read overlap in the banks.
-constexpr int bwd_row_stride(int d) { return d == 128 ? d + 24 : d + 40; }
+constexpr int bwd_row_stride(int d) { return d >= 128 ? d + 24 : d + 40; }
 
 // ---------------------------------------------------------------------------------------
 template <typename Tag, int D>
@@ -61,7 +61,7 @@ fa_bwd_preprocess_kernel(const uint16_t* __restrict__ o, const uint16_t* __restr
 
 // ---------------------------------------------------------------------------------------
 template <typename Tag, int D, bool CAUSAL>
-__global__ void __launch_bounds__(256, D == 128 ? 1 : 2)
+__global__ void __launch_bounds__(256, D >= 128 ? 1 : 2)
 fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
               const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
               uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
@@ -74,10 +74,16 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     // gives 208 / 63, 320 B gives 63 / 208.
     constexpr int RSTR = bwd_row_stride(D);
     constexpr int KS = D / 16;
-    constexpr int DT = D / 32;
+    // S and dP contract over the whole head dimension; dK and dV are produced for a slice of DO
+    // columns per workgroup (the whole of it up to d = 128; at d = 256 two workgroups, blockIdx.y,
+    // take half each and both recompute S and dP -- the accumulators of all 256 columns, 256
+    // registers per lane on top of the K and V operands, do not fit the register file)
+    constexpr int DO = D > 128 ? 128 : D;
+    constexpr int DT = DO / 32;
     constexpr int CPR = D / 8;     // 16-byte chunks per row
     constexpr int QCH = BQ * CPR / NT;  // chunks per thread for a Q / dO tile
     using E = Elem<Tag>;
+    const int col0 = blockIdx.y * DO;  // first column of this workgroup's slice
 
     __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][BQ * RSTR];
     __shared__ __attribute__((aligned(16))) uint16_t lds_do[2][BQ * RSTR];
@@ -112,7 +118,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     // half of the register file, which only MFMA can address directly.  K_j / V_j operands and the
     // dK / dV accumulators are touched by MFMA alone: pin the operands there so that the score
     // tiles, which the exponentials read, stay in ordinary registers and need no copies.
-    if constexpr (D == 128) {
+    if constexpr (D >= 128) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(kreg[ks]), "+a"(vreg[ks]));
     }
@@ -260,13 +266,14 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                     if (sub == 1) {
                         // the 8 register pairs of sub-tile 0 spread over the KS steps; the L, D group
                         // of a pair is fetched one step before the step that needs it first
-                        constexpr int PP = 8 / KS;
+                        // pair c runs at step c KS / 8
 #pragma unroll
                         for (int g = 1; g < 4; ++g)
-                            if ((2 * g) / PP == ks + 1) fetch_ld(0, g);
+                            if ((2 * g * KS) / 8 == ks + 1) fetch_ld(0, g);
                         if (ks == KS - 1) fetch_ld(1, 0);
 #pragma unroll
-                        for (int p = 0; p < PP; ++p) softmax_pair(0, ks * PP + p);
+                        for (int c = 0; c < 8; ++c)
+                            if ((c * KS) / 8 == ks) softmax_pair(0, c);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -276,7 +283,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
             {
                 constexpr int NU = 2 * 2 * DT;  // (sub, slab, d-tile)
                 const int rbase = (4 * half + tr_row) * RSTR + tr_col;
-                auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + (u % DT) * 32; };
+                auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + col0 + (u % DT) * 32; };
                 i32x2 dlo[kPipe], dhi[kPipe], qlo[kPipe], qhi[kPipe];
 #pragma unroll
                 for (int u = 0; u < kPipe; ++u) {
@@ -328,7 +335,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         for (int r = 0; r < 16; ++r) {
             int key = key0 + wave * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
             if (key < N) {
-                size_t off = head_off + (size_t)key * D + dt * 32 + col;
+                size_t off = head_off + (size_t)key * D + col0 + dt * 32 + col;
                 dk[off] = (uint16_t)(E::pack2(dkacc[dt][r] * scale, 0.f) & 0xFFFF);
                 dv[off] = (uint16_t)(E::pack2(dvacc[dt][r], 0.f) & 0xFFFF);
             }
@@ -338,7 +345,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
 // ---------------------------------------------------------------------------------------
 // dQ pass: the forward kernel's structure with dO alongside Q and K^T in place of V^T.
 template <typename Tag, int D, int BC, int NW, bool CAUSAL>
-__global__ void __launch_bounds__(NW * 64, 2)
+__global__ void __launch_bounds__(NW * 64, NW == 8 ? 2 : 1)
 fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
                  uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, int kv_group, float scale) {
@@ -517,17 +524,18 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
 
     int n_kblocks = (N + 127) / 128;
     long total = (long)B * H_kv * n_kblocks;
+    const dim3 kv_grid((unsigned)total, D > 128 ? D / 128 : 1);  // y: 128-column slices of dK, dV
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     if (causal)
-        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, true>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, true>), kv_grid, dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
     else
-        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, false>), dim3((unsigned)total), dim3(256), 0, stream, u16(q),
+        hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, false>), kv_grid, dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
 
-    constexpr int BC = 64, NW = 8;
+    constexpr int BC = 64, NW = D == 256 ? 4 : 8;  // d = 256: a wave needs the whole register file
     int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
     long total_q = (long)B * H * n_qtiles;
     if (causal)
@@ -550,6 +558,8 @@ int launch_bwd(const void* q, const void* k, const void* v, const void* o, const
     if (dtype == FA_BF16 && d == 64) FA_BWD_CASE(bf16_tag, 64);
     if (dtype == FA_F16 && d == 128) FA_BWD_CASE(f16_tag, 128);
     if (dtype == FA_F16 && d == 64) FA_BWD_CASE(f16_tag, 64);
+    if (dtype == FA_BF16 && d == 256) FA_BWD_CASE(bf16_tag, 256);
+    if (dtype == FA_F16 && d == 256) FA_BWD_CASE(f16_tag, 256);
 #undef FA_BWD_CASE
     return FA_ERR_UNSUPPORTED;
 }

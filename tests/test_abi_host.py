@@ -59,9 +59,10 @@ def test_fp8_and_bwd_entry_points_validate():
     assert L.fa_fp8_quant_hadamard(p, binding.FA_FP8_E4M3, p, p, 1, 1, 16, 128, 128, None, 0, None) == 4
     assert L.fa_fp8_quant_hadamard(p, 9, p, p, 1, 1, 16, 128, 128, None, 0, None) == 3
     assert L.fa_fp8_quant_hadamard(p, binding.FA_BF16, p, p, 1, 1, 0, 128, 128, None, 0, None) == 2
-    assert L.fa_bwd_workspace_bytes(1, 1, 16, 256, binding.FA_BF16) == 0  # unsupported head dim
+    assert L.fa_bwd_workspace_bytes(1, 1, 16, 96, binding.FA_BF16) == 0  # unsupported head dim
     assert L.fa_bwd_workspace_bytes(1, 1, 16, 64, binding.FA_BF16) == 64
-    args = [p] * 10 + [0, 1, 1, 16, 256, 0.1, 0, binding.FA_BF16, None]
+    assert L.fa_bwd_workspace_bytes(1, 1, 16, 256, binding.FA_F32) == 0  # unsupported dtype
+    args = [p] * 10 + [0, 1, 1, 16, 256, 0.1, 0, binding.FA_F32, None]
     assert L.fa_bwd(*args) == 4
     args = [p] * 9 + [None, 0, 1, 1, 16, 128, 0.1, 0, binding.FA_BF16, None]
     assert L.fa_bwd(*args) == 6
