@@ -118,6 +118,24 @@ def test_gqa_backward(N, H, H_kv, causal, dtype):
     _compare(dv, ref["dv"], "dv")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("H,H_kv", [(4, 2), (3, 1)])
+@pytest.mark.parametrize("d", [64, 256])
+def test_gqa_backward_other_head_dims(d, H, H_kv, causal):
+    B, N = 2, 333
+    q, k, v = _tensors(160 + d + H, B, H, H_kv, N, d, "bf16")
+    dout = inputs.normal_tensor(161 + d, "do", (B, H, N, d), "bf16")
+    scale = d ** -0.5
+    qg, kg, vg, dog = (t.cuda() for t in (q, k, v, dout))
+    o, lse = binding.fa_fwd_gqa(qg, kg, vg, scale, causal)
+    dq, dk, dv = binding.fa_bwd_gqa(qg, kg, vg, o, lse, dog, scale, causal)
+    torch.cuda.synchronize()
+    ref = oracle.attention_bwd_gqa(f64(q), f64(k), f64(v), f64(dout), scale, causal)
+    _compare(dq, ref["dq"], "dq")
+    _compare(dk, ref["dk"], "dk")
+    _compare(dv, ref["dv"], "dv")
+
+
 def test_gqa_backward_is_repeatable_and_rejects_bad_groups():
     B, H, H_kv, N, d = 1, 4, 2, 700, 128
     q, k, v = (t.cuda() for t in _tensors(140, B, H, H_kv, N, d, "bf16"))
