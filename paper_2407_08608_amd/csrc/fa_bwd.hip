@@ -1,4 +1,4 @@
-// Backward attention for gfx950, head dimensions 64 and 128, bf16 / fp16 (paper section 2.1 chain rule,
+// Backward attention for gfx950, head dimensions 64, 128 and 256, bf16 / fp16 (paper section 2.1 chain rule,
 // Algorithm 3's recomputation of P from L and its D = rowsum(dO o O)).
 //
 //   preprocess : D = rowsum(dO o O) per query row (HBM-bound)
