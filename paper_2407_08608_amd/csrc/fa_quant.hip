@@ -54,15 +54,20 @@ static __device__ __forceinline__ void load_chunk(const void* base, size_t elem_
 // MODE 0: per-block scales.  MODE 1: only fold the block's amax into *amax_bits (atomic max on
 // the bit pattern of a non-negative float).  MODE 2: quantise with the scale taken from
 // *amax_bits, leave `scales` alone.
+// Lanes per row: d / 16 (at least 4), so that a lane holds 32 values of the 128-row block whatever
+// the head dimension and six waves fit a SIMD: the kernel is bound by memory latency otherwise.
+constexpr int quant_lanes_per_row(int d) { return d >= 64 ? (d / 16 < 4 ? 4 : d / 16) : 4; }
+
 template <int D, int IN_DTYPE, int MODE, bool HADAMARD>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(64 * quant_lanes_per_row(D))
 fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __restrict__ scales,
                 const signed char* __restrict__ signs, unsigned* amax_bits, int N, int n_blocks) {
-    constexpr int CH = D / 32;        // 8-element chunks per lane (4 lanes per row)
+    constexpr int LPR = quant_lanes_per_row(D);
+    constexpr int CH = D / (8 * LPR);        // 8-element chunks per lane
     constexpr int PASSES = kBlockRows / 64;  // 64 rows per pass over the workgroup
     const int tid = threadIdx.x;
-    const int p = tid & 3;            // lane within the row's quad
-    const int row_in_pass = tid >> 2;
+    const int p = tid & (LPR - 1);    // lane within the row's group
+    const int row_in_pass = tid / LPR;
     const int bh = blockIdx.x / n_blocks, blk = blockIdx.x % n_blocks;
     const size_t head_off = (size_t)bh * N * D;
     const float inv_sqrt_d = (float)(1.0 / __builtin_sqrt((double)D));
@@ -72,7 +77,7 @@ fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __r
 #pragma unroll
         for (int c = 0; c < CH; ++c)
 #pragma unroll
-            for (int t = 0; t < 8; ++t) sg[c][t] = (float)signs[8 * (p + 4 * c) + t];
+            for (int t = 0; t < 8; ++t) sg[c][t] = (float)signs[8 * (p + LPR * c) + t];
     }
 
     float y[PASSES][CH][8];
@@ -83,14 +88,14 @@ fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __r
 #pragma unroll
         for (int c = 0; c < CH; ++c) {
             if (row < N) {
-                load_chunk<IN_DTYPE>(x, head_off + (size_t)row * D + 8 * (p + 4 * c), y[ps][c]);
+                load_chunk<IN_DTYPE>(x, head_off + (size_t)row * D + 8 * (p + LPR * c), y[ps][c]);
             } else {
 #pragma unroll
                 for (int t = 0; t < 8; ++t) y[ps][c][t] = 0.f;
             }
         }
         if constexpr (HADAMARD) {
-            // element index e = t + 8*p + 32*c
+            // element index e = t + 8*p + 8*LPR*c
 #pragma unroll
             for (int c = 0; c < CH; ++c) {
 #pragma unroll
@@ -114,10 +119,23 @@ fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __r
                     float v = y[ps][c][t];
                     v = __builtin_fmaf(v, s1, quad_perm<0xB1>(v));  // lanes (1,0,3,2)
                     v = __builtin_fmaf(v, s2, quad_perm<0x4E>(v));  // lanes (2,3,0,1)
+                    // strides 32 and 64: partner lanes p^4, p^8 (swizzle within 32 lanes: and 0x1f, or 0, xor)
+                    if constexpr (LPR >= 8) {
+                        const float s3 = (p & 4) ? -1.f : 1.f;
+                        const float other = __builtin_bit_cast(
+                            float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), (4 << 10) | 0x1f));
+                        v = __builtin_fmaf(v, s3, other);
+                    }
+                    if constexpr (LPR >= 16) {
+                        const float s4 = (p & 8) ? -1.f : 1.f;
+                        const float other = __builtin_bit_cast(
+                            float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), (8 << 10) | 0x1f));
+                        v = __builtin_fmaf(v, s4, other);
+                    }
                     y[ps][c][t] = v;
                 }
 #pragma unroll
-            for (int h = 1; h < CH; h <<= 1)  // strides 32, 64, 128
+            for (int h = 1; h < CH; h <<= 1)  // strides 8 LPR h: 32, 64, 128 (64, 128 with eight lanes per row)
 #pragma unroll
                 for (int c = 0; c < CH; ++c)
                     if ((c & h) == 0)
@@ -139,12 +157,15 @@ fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __r
     }
 
     // block amax
-    __shared__ float red[4];
+    static_assert(LPR <= 16, "the lane exchanges above cover up to sixteen lanes per row");
+    __shared__ float red[LPR];  // one slot per wave
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
     if ((tid & 63) == 0) red[tid >> 6] = amax;
     __syncthreads();
-    amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    amax = red[0];
+#pragma unroll
+    for (int w = 1; w < LPR; ++w) amax = fmaxf(amax, red[w]);
 
     if constexpr (MODE == 1) {
         if (tid == 0) atomicMax(amax_bits, __builtin_bit_cast(unsigned, amax));
@@ -174,7 +195,7 @@ fa_quant_kernel(const void* __restrict__ x, uint8_t* __restrict__ x8, float* __r
             w1 = __builtin_amdgcn_cvt_pk_fp8_f32(z[4], z[5], w1, false);
             w1 = __builtin_amdgcn_cvt_pk_fp8_f32(z[6], z[7], w1, true);
             i32x2 w = {w0, w1};
-            *reinterpret_cast<i32x2*>(x8 + head_off + (size_t)row * D + 8 * (p + 4 * c)) = w;
+            *reinterpret_cast<i32x2*>(x8 + head_off + (size_t)row * D + 8 * (p + LPR * c)) = w;
         }
     }
 }
@@ -195,7 +216,7 @@ static int launch_quant(const void* x, void* x8, float* scales, int B, int H, in
     int n_blocks = (N + kBlockRows - 1) / kBlockRows;
     long total = (long)B * H * n_blocks;
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
-    dim3 grid((unsigned)total), block(256);
+    dim3 grid((unsigned)total), block(64 * quant_lanes_per_row(D));
     auto out = static_cast<uint8_t*>(x8);
     unsigned* slot0 = reinterpret_cast<unsigned*>(scales);
     if (!per_tensor) {
