@@ -170,3 +170,18 @@ def test_calls_follow_the_current_stream_and_reuse_caller_buffers():
     side.synchronize()
     assert o2.data_ptr() == o.data_ptr() and l2.data_ptr() == lse.data_ptr()
     assert torch.equal(o, o_ref) and torch.equal(lse, l_ref)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_bf16_long_ragged_sequence_sampled_rows(causal):
+    # longer than any benchmark shape and not a multiple of any tile: 625 key blocks, 157 query tiles
+    # (an odd count, so the causal pairing leaves a middle tile on its own)
+    B, H, N, d = 1, 2, 40001, 128
+    q, k, v = inputs.qkv(97, B, H, N, d, "bf16")
+    o, lse = _run(q, k, v, d ** -0.5, causal)
+    rows = np.concatenate([inputs.sample_rows(98, B * H * N, 192), np.array([0, N - 1, N, 2 * N - 1])])
+    rows = np.unique(rows)
+    o_ref, l_ref = oracle.attention_fwd_rows(f64(q), f64(k), f64(v), rows, d ** -0.5, causal)
+    assert max_abs(gpu_rows(o, rows), o_ref) <= O_MAXABS and rmse(gpu_rows(o, rows), o_ref) <= O_RMSE
+    assert max_abs(gpu_rows(lse, rows), l_ref) <= L_MAXABS
+    assert bool(torch.isfinite(o).all())
