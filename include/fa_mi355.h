@@ -24,6 +24,9 @@
  *   - Supported head dimensions: d in {64, 128, 256}.  N >= 1 (any N; rows past N are
  *     never read or written).  B, H >= 1.  scale finite and > 0.  causal in {0, 1};
  *     causal means key j is visible to query i iff j <= i (N_q == N_k).
+ *   - Size limits: B*H*N < 2^31 rows (else FA_ERR_SHAPE) and, because one head is
+ *     addressed through 32-bit byte offsets, 4*N*d <= 0x7ff00000 (else
+ *     FA_ERR_UNSUPPORTED): N <= 4 192 256 at d = 128, twice that at d = 64, half at 256.
  *   - Thread-safe: no mutable global state.
  */
 #ifndef FA_MI355_H

@@ -46,6 +46,10 @@ def _load():
         lib.oracle_attn_fwd_rows.restype = None
         lib.oracle_attn_bwd.argtypes = [dp] * 10 + [ci, ci, ci, ci, cd, ci]
         lib.oracle_attn_bwd.restype = None
+        lib.oracle_attn_bwd_dq_rows.argtypes = [dp, dp, dp, dp, ip, cl, dp, ci, ci, ci, ci, cd, ci]
+        lib.oracle_attn_bwd_dq_rows.restype = None
+        lib.oracle_attn_bwd_dkdv_keys.argtypes = [dp, dp, dp, dp, ci, ci, dp, dp, ci, ci, cd, ci]
+        lib.oracle_attn_bwd_dkdv_keys.restype = None
         lib.oracle_attn_probs.argtypes = [dp, dp, dp, dp, ci, ci, cd, ci]
         lib.oracle_attn_probs.restype = None
         _lib = lib
@@ -101,6 +105,33 @@ def attention_bwd(q, k, v, dout, alpha, causal):
     _load().oracle_attn_bwd(_p(q), _p(k), _p(v), _p(dout), _p(o), _p(lse), _p(D), _p(dq), _p(dk), _p(dv),
                             B, H, N, d, float(alpha), int(bool(causal)))
     return dict(o=o, lse=lse, D=D, dq=dq, dk=dk, dv=dv)
+
+
+def attention_bwd_dq_rows(q, k, v, dout, rows, alpha, causal):
+    """dQ of the flat query rows `rows` (into B*H*N) only, [n,d]: the row-by-row arithmetic of
+    `attention_bwd`, for problems too long to differentiate whole."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    B, H, N, d = q.shape
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.ndim == 1 and (rows.size == 0 or (rows.min() >= 0 and rows.max() < B * H * N))
+    dq = np.empty((rows.size, d), dtype=np.float64)
+    _load().oracle_attn_bwd_dq_rows(_p(q), _p(k), _p(v), _p(dout), rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                    rows.size, _p(dq), B, H, N, d, float(alpha), int(bool(causal)))
+    return dq
+
+
+def attention_bwd_dkdv_keys(q, k, v, dout, j0, j1, alpha, causal):
+    """dK and dV ([j1-j0, d] each) of the key rows j0..j1-1 of a single head (q, k, v, dout: [N,d]).
+    Under the causal mask only the queries from j0 on reach these keys, so the last keys of a long
+    sequence cost a few full rows."""
+    q, k, v, dout = _f64(q), _f64(k), _f64(v), _f64(dout)
+    N, d = q.shape
+    assert 0 <= j0 <= j1 <= N
+    dk = np.empty((j1 - j0, d), dtype=np.float64)
+    dv = np.empty((j1 - j0, d), dtype=np.float64)
+    _load().oracle_attn_bwd_dkdv_keys(_p(q), _p(k), _p(v), _p(dout), int(j0), int(j1), _p(dk), _p(dv), N, d,
+                                      float(alpha), int(bool(causal)))
+    return dk, dv
 
 
 def attention_probs(q, k, v, alpha, causal):

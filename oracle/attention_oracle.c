@@ -164,6 +164,91 @@ void oracle_attn_bwd(const double *q, const double *k, const double *v, const do
     }
 }
 
+/* dQ of sampled query rows only (same arithmetic as oracle_attn_bwd, one row at a time):
+ * rows[t] is a flat index into B*H*N; dq_rows is [n_rows, d].  Cost O(n_rows N d). */
+void oracle_attn_bwd_dq_rows(const double *q, const double *k, const double *v, const double *dout,
+                             const int64_t *rows, long n_rows, double *dq_rows, int B, int H, int N, int d,
+                             double alpha, int causal) {
+    (void)B;
+    (void)H;
+    size_t hsz = (size_t)N * d;
+#pragma omp parallel
+    {
+        double *p = (double *)malloc(sizeof(double) * (size_t)N);
+        double *oi = (double *)malloc(sizeof(double) * (size_t)d);
+#pragma omp for schedule(dynamic, 1)
+        for (long t = 0; t < n_rows; ++t) {
+            long bh = rows[t] / N;
+            int i = (int)(rows[t] % N);
+            const double *Kh = k + bh * hsz, *Vh = v + bh * hsz;
+            const double *qi = q + bh * hsz + (size_t)i * d, *doi = dout + bh * hsz + (size_t)i * d;
+            double *dqi = dq_rows + (size_t)t * d, lse;
+            attention_row(qi, Kh, Vh, N, d, alpha, causal, i, oi, &lse, p);
+            double D = 0.0;
+            for (int c = 0; c < d; ++c) D += doi[c] * oi[c];
+            for (int c = 0; c < d; ++c) dqi[c] = 0.0;
+            int nvis = causal ? (i + 1) : N;
+            for (int j = 0; j < nvis; ++j) {
+                const double *kj = Kh + (size_t)j * d, *vj = Vh + (size_t)j * d;
+                double dp = 0.0;
+                for (int c = 0; c < d; ++c) dp += doi[c] * vj[c];
+                double ds = p[j] * (dp - D);
+                for (int c = 0; c < d; ++c) dqi[c] += alpha * ds * kj[c];
+            }
+        }
+        free(p);
+        free(oi);
+    }
+}
+
+/* dK and dV of the key rows [j0, j1) of ONE head (q, k, v, dout: [N, d]; dk, dv: [j1-j0, d]).
+ * Every query that sees one of these keys contributes: all N of them without a mask, the
+ * queries i >= j0 under the causal mask -- so for keys near the end of a long causal problem
+ * this costs O((N - j0) N d) instead of O(N^2 d). */
+void oracle_attn_bwd_dkdv_keys(const double *q, const double *k, const double *v, const double *dout, int j0,
+                               int j1, double *dk, double *dv, int N, int d, double alpha, int causal) {
+    size_t outsz = (size_t)(j1 - j0) * d;
+    memset(dk, 0, sizeof(double) * outsz);
+    memset(dv, 0, sizeof(double) * outsz);
+#pragma omp parallel
+    {
+        double *p = (double *)malloc(sizeof(double) * (size_t)N);
+        double *oi = (double *)malloc(sizeof(double) * (size_t)d);
+        double *dkt = (double *)calloc(outsz + 1, sizeof(double)); /* this thread's share */
+        double *dvt = (double *)calloc(outsz + 1, sizeof(double));
+#pragma omp for schedule(dynamic, 1)
+        for (int i = causal ? j0 : 0; i < N; ++i) {
+            const double *qi = q + (size_t)i * d, *doi = dout + (size_t)i * d;
+            double lse;
+            attention_row(qi, k, v, N, d, alpha, causal, i, oi, &lse, p);
+            double D = 0.0;
+            for (int c = 0; c < d; ++c) D += doi[c] * oi[c];
+            int nvis = causal ? (i + 1) : N;
+            for (int j = j0; j < j1 && j < nvis; ++j) {
+                const double *vj = v + (size_t)j * d;
+                double dp = 0.0;
+                for (int c = 0; c < d; ++c) dp += doi[c] * vj[c];
+                double ds = p[j] * (dp - D);
+                for (int c = 0; c < d; ++c) {
+                    dkt[(size_t)(j - j0) * d + c] += alpha * ds * qi[c];
+                    dvt[(size_t)(j - j0) * d + c] += p[j] * doi[c];
+                }
+            }
+        }
+#pragma omp critical
+        {
+            for (size_t t = 0; t < outsz; ++t) {
+                dk[t] += dkt[t];
+                dv[t] += dvt[t];
+            }
+        }
+        free(p);
+        free(oi);
+        free(dkt);
+        free(dvt);
+    }
+}
+
 /* The probability matrix of one head, P[N, N] (for invariants such as rows summing to 1). */
 void oracle_attn_probs(const double *q, const double *k, const double *v, double *P, int N, int d,
                        double alpha, int causal) {

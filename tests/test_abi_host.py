@@ -49,6 +49,9 @@ def test_fa_fwd_rejects_bad_arguments_without_launching():
     assert call(d=96) == 4
     assert call(dtype=binding.FA_F32, d=128, q=ctypes.c_void_p(0x1008)) == 5
     assert call(k=ctypes.c_void_p(0x1004)) == 5
+    # documented size limits: B*H*N below 2^31 rows, 4*N*d below 0x7ff00000 bytes per head
+    assert call(B=2048, H=1024, N=1024) == 2
+    assert call(N=0x7ff00000 // (4 * 128) + 1, d=128) == 4 and call(N=0x7ff00000 // (4 * 64) + 1, d=64) == 4
 
 
 def test_fp8_and_bwd_entry_points_validate():

@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import oracle
-from helpers import f64, max_abs, rmse
+from helpers import f64, gpu_rows, max_abs, rmse
 from paper_2407_08608_amd import binding, inputs
 
 pytestmark = pytest.mark.gpu
@@ -99,3 +99,34 @@ def test_bwd_benchmark_shapes_sampled_heads(N, d, causal):
         _compare(dq[sl], ref["dq"], f"dq[{b},{h}]")
         _compare(dk[sl], ref["dk"], f"dk[{b},{h}]")
         _compare(dv[sl], ref["dv"], f"dv[{b},{h}]")
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_bwd_long_ragged_sequence_sampled(causal):
+    """Half a million keys, not a multiple of any tile: far longer than the oracle can differentiate
+    whole, so it checks dQ on sampled query rows and, under the causal mask, dK and dV of the last
+    205 keys (the ragged last key block and the full one before it), which only the last queries
+    reach.  Those tail gradients are tiny (P ~ 1/N), so they are compared relative to their own size."""
+    B, H, N, d = 1, 2, 524288 + 77, 128
+    q, k, v = inputs.qkv(90, B, H, N, d, "bf16")
+    dout = inputs.normal_tensor(91, "do", (B, H, N, d), "bf16")
+    scale = d ** -0.5
+    dq, dk, dv = _gpu_bwd(q, k, v, dout, scale, causal)
+    assert all(bool(torch.isfinite(t).all()) for t in (dq, dk, dv))
+    q64, k64, v64, do64 = f64(q), f64(k), f64(v), f64(dout)
+    rows = np.unique(np.concatenate([inputs.sample_rows(92, B * H * N, 60), [1, N - 1, N, 2 * N - 1]])).astype(np.int64)
+    ref = oracle.attention_bwd_dq_rows(q64, k64, v64, do64, rows, scale, causal)
+    got = gpu_rows(dq, rows)
+    ref_rms = float(np.sqrt(np.mean(ref * ref)))
+    assert rmse(got, ref) <= REL_RMSE * ref_rms and max_abs(got, ref) <= REL_MAXABS * np.abs(ref).max(), \
+        (rmse(got, ref), ref_rms, max_abs(got, ref))
+    if causal:
+        j0 = N - 77 - 128
+        for h in range(H):
+            dk_ref, dv_ref = oracle.attention_bwd_dkdv_keys(q64[0, h], k64[0, h], v64[0, h], do64[0, h], j0, N,
+                                                            scale, True)
+            for name, g, r in (("dk", dk, dk_ref), ("dv", dv, dv_ref)):
+                g = f64(g[0, h, j0:])
+                r_rms = float(np.sqrt(np.mean(r * r)))
+                assert rmse(g, r) <= REL_RMSE * r_rms and max_abs(g, r) <= REL_MAXABS * np.abs(r).max(), \
+                    (name, h, rmse(g, r), r_rms, max_abs(g, r))

@@ -170,6 +170,28 @@ def test_fp8_unit_scale_entry_point_and_constant_values():
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("H,N,d", [(16, 16384, 128), (8, 16384, 256), (32, 16384, 64), (16, 4096, 128)])
+def test_fp8_benchmark_shapes_sampled_rows(H, N, d, causal):
+    """The shapes the benchmark times (section 4.1: 16k tokens in total, hidden size 2048), in the
+    kernel and launch configuration it times; sampled output rows against the model oracle."""
+    B = 16384 // N
+    _, codes, scales = _prepare(70 + d, B, H, N, d, heavy=False)
+    scale = d ** -0.5
+    o, lse = _fwd_fp8_gpu(codes, scales, scale, causal)
+    assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
+    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
+    rows = inputs.sample_rows(71 + d, B * H * N, 384)
+    # the first and the last rows of a head, and both sides of a 128-row scale block boundary
+    rows = np.unique(np.concatenate([rows, [0, 1, 127, 128, N - 1, N, B * H * N - 1]])).astype(np.int64)
+    o_ref, l_ref = oracle.attention_fwd_rows(*deq, rows, scale, causal)
+    got = gpu_rows(o, rows)
+    assert max_abs(got, o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
+    # long rows average the P~ rounding down; causal rows are as short as one key
+    assert rmse(got, o_ref) <= (8e-3 if causal else 2e-3)
+    assert max_abs(gpu_rows(lse, rows), l_ref) <= 2e-3
+
+
+@pytest.mark.parametrize("causal", [False, True])
 def test_fp8_error_ordering_on_heavy_tailed_inputs_full_gpu_path(causal):
     """Section 4.3 / Table 3: quantisation pre-pass and forward both on the GPU, error against
     fp64 attention on the original inputs; d=128, N=4096 point of the sweep, sampled rows."""

@@ -15,6 +15,14 @@ from paper_2407_08608_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 O_MAXABS, O_RMSE, L_MAXABS = 2e-2, 3e-3, 2e-3
+# Long non-causal rows average N values of V, so |O| ~ N^-1/2 and the absolute targets above stop
+# biting; there the error is also held relative to the reference's own RMS.  The bf16 store alone
+# gives 2^-9 / sqrt(3) = 1.1e-3, P~ rounding averages out over the row.
+O_REL_RMSE = 5e-3
+
+
+def _rel_rmse_ok(got, ref):
+    return rmse(got, ref) <= O_REL_RMSE * float(np.sqrt(np.mean(np.square(ref))))
 
 
 def _run(q, k, v, scale, causal):
@@ -121,6 +129,7 @@ def test_bf16_benchmark_shapes_sampled_rows(N, d, causal):
     r_o = rmse(gpu_rows(o, rows), o_ref)
     e_l = max_abs(gpu_rows(lse, rows), l_ref)
     assert e_o <= O_MAXABS and r_o <= O_RMSE and e_l <= L_MAXABS, (e_o, r_o, e_l)
+    assert _rel_rmse_ok(gpu_rows(o, rows), o_ref)
     # property that holds at any size: nothing non-finite anywhere in the full output
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
 
@@ -184,4 +193,21 @@ def test_bf16_long_ragged_sequence_sampled_rows(causal):
     o_ref, l_ref = oracle.attention_fwd_rows(f64(q), f64(k), f64(v), rows, d ** -0.5, causal)
     assert max_abs(gpu_rows(o, rows), o_ref) <= O_MAXABS and rmse(gpu_rows(o, rows), o_ref) <= O_RMSE
     assert max_abs(gpu_rows(lse, rows), l_ref) <= L_MAXABS
+    assert _rel_rmse_ok(gpu_rows(o, rows), o_ref)
     assert bool(torch.isfinite(o).all())
+
+
+@pytest.mark.parametrize("N,d,causal", [(1048576 + 77, 128, False), (1048576 + 77, 128, True), (1048576 + 77, 64, True),
+                                        (524288 + 77, 256, True)])
+def test_bf16_million_key_ragged_sequence_sampled_rows(N, d, causal):
+    # a quarter of the longest sequence the entry point accepts at d = 128 (4 bytes x N x d below 2^31):
+    # byte offsets inside one head pass 2^28, 16k key blocks per row
+    B, H = 1, 1
+    q, k, v = inputs.qkv(99, B, H, N, d, "bf16")
+    o, lse = _run(q, k, v, d ** -0.5, causal)
+    rows = np.unique(np.concatenate([inputs.sample_rows(100, N, 96), [0, 1, 255, 256, N - 78, N - 77, N - 1]]))
+    o_ref, l_ref = oracle.attention_fwd_rows(f64(q), f64(k), f64(v), rows.astype(np.int64), d ** -0.5, causal)
+    assert max_abs(gpu_rows(o, rows), o_ref) <= O_MAXABS and rmse(gpu_rows(o, rows), o_ref) <= O_RMSE
+    assert max_abs(gpu_rows(lse, rows), l_ref) <= L_MAXABS
+    assert _rel_rmse_ok(gpu_rows(o, rows), o_ref)
+    assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())

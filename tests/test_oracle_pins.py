@@ -236,6 +236,29 @@ def test_backward_constant_values_have_zero_query_key_gradients():
     np.testing.assert_allclose(g["dv"].sum(axis=2), dout.sum(axis=2), rtol=1e-12)
 
 
+@pytest.mark.parametrize("causal", [False, True])
+def test_backward_restricted_to_rows_and_key_ranges(causal):
+    """The row-sampled dQ and the key-range dK/dV (used where the whole problem is too long to
+    differentiate on the CPU) against matrix products written with numpy from P, and against the
+    whole-tensor backward."""
+    B, H, N, d = 2, 2, 23, 8
+    q, k, v, dout = (_rand(s, B, H, N, d) for s in (52, 53, 54, 55))
+    alpha = 0.4
+    g = oracle.attention_bwd(q, k, v, dout, alpha, causal)
+    rows = np.array([0, 5, N - 1, N, 2 * N + 7, B * H * N - 1], dtype=np.int64)
+    dq_rows = oracle.attention_bwd_dq_rows(q, k, v, dout, rows, alpha, causal)
+    np.testing.assert_allclose(dq_rows, g["dq"].reshape(-1, d)[rows], rtol=1e-12, atol=1e-14)
+    for b, hh, j0, j1 in ((0, 0, 0, N), (1, 1, 17, N), (0, 1, 9, 14), (1, 0, N - 1, N), (1, 0, 4, 4)):
+        dk, dv = oracle.attention_bwd_dkdv_keys(q[b, hh], k[b, hh], v[b, hh], dout[b, hh], j0, j1, alpha, causal)
+        P = oracle.attention_probs(q[b, hh], k[b, hh], v[b, hh], alpha, causal)
+        dP = dout[b, hh] @ v[b, hh].T
+        dS = P * (dP - np.sum(P * dP, axis=1, keepdims=True))
+        np.testing.assert_allclose(dk, (alpha * dS.T @ q[b, hh])[j0:j1], rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(dv, (P.T @ dout[b, hh])[j0:j1], rtol=1e-10, atol=1e-13)
+        np.testing.assert_allclose(dk, g["dk"][b, hh, j0:j1], rtol=1e-12, atol=1e-14)
+        np.testing.assert_allclose(dv, g["dv"][b, hh, j0:j1], rtol=1e-12, atol=1e-14)
+
+
 # ---- multi-query / grouped-query attention (section 3.1, "Attention variants") -------------------------
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("H,H_kv", [(4, 4), (4, 2), (6, 2), (3, 1)])
