@@ -56,6 +56,9 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="for rocprofv3 --pmc runs: a plain 256 MiB device copy (calibration) followed by the "
                          "six non-causal forward launches, three times each; prints nothing")
+    ap.add_argument("--counter-probe", choices=("bwd", "fp8"),
+                    help="for rocprofv3 --pmc runs: three launches of the bf16 backward (bwd) or of the block-scaled "
+                         "FP8 forward (fp8) at seqlen 16k, d = 128, non-causal; prints nothing")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="instead of the benchmark: the MFMA-only rate of the chip (bf16 and e4m3) on constant and "
                          "on random operand bits; prints one JSON line")
@@ -73,6 +76,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.mfma_probe:
         print(json.dumps(mfma_probe(torch, binding, inputs, dev)))
+        return
+    if args.counter_probe:
+        counter_probe(torch, binding, inputs, dev, args.counter_probe)
         return
     d = HEAD_DIM
     scale = d ** -0.5
@@ -188,6 +194,26 @@ def mfma_probe(torch, binding, inputs, dev):
         ms = _time_call(torch, lambda: binding.fa_probe_mfma(t, code, iters), reps=8, warm=4)
         out[f"{name}_{kind}"] = round(binding.fa_probe_mfma_flops(code, iters) / ms / 1e9, 1)
     return out
+
+
+def counter_probe(torch, binding, inputs, dev, which):
+    """Three launches of one more kernel family for hardware-counter runs (seqlen 16k, d = 128, non-causal)."""
+    N, d = 16384, 128
+    B, H = inputs.benchmark_shape(N, d)
+    q, k, v = (t.to(dev) for t in inputs.qkv(7, B, H, N, d, "bf16"))
+    if which == "bwd":
+        do = inputs.normal_tensor(8, "do", (B, H, N, d), "bf16").to(dev)
+        o, lse = binding.fa_fwd(q, k, v, d ** -0.5, False)
+        for _ in range(3):
+            binding.fa_bwd(q, k, v, o, lse, do, d ** -0.5, False)
+    else:
+        signs = inputs.random_signs(7, d).to(dev)
+        q8, qs = binding.fa_fp8_quant_hadamard(q, signs)
+        k8, ks = binding.fa_fp8_quant_hadamard(k, signs)
+        v8, vs = binding.fa_fp8_quant_hadamard(v, None)
+        for _ in range(3):
+            binding.fa_fwd_fp8(q8, k8, v8, qs, ks, vs, d ** -0.5, False)
+    torch.cuda.synchronize()
 
 
 def _time_call(torch, fn, reps=10, warm=2):

@@ -27,7 +27,6 @@
 
 namespace fa {
 
-constexpr int kPipe = 2;  // MFMA steps by which LDS operand reads lead their use
 
 // LDS row stride (elements) of tiles that are read both by rows and transposed: an odd multiple
 // of 16 bytes keeps the row reads conflict-free, and the offset from a multiple of 256 bytes
@@ -71,9 +70,17 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     constexpr int NT = 256;
     // Row stride of the Q and dO tiles: they are read both as rows (128-bit) and transposed.
     // Measured LDS rates per CU at D = 128: 304 B gives 211 / 123 B/clk (rows / transposed), 272 B
-    // gives 208 / 63, 320 B gives 63 / 208.
+    // gives 208 / 63, 320 B gives 63 / 208.  (An unpadded XOR-swizzled layout that frees both
+    // reads of bank conflicts altogether was measured too: same speed, the kernel is bound by
+    // the instruction issue of its one wave per SIMD, not by the LDS.)
     constexpr int RSTR = bwd_row_stride(D);
+    constexpr int TILE_B = BQ * RSTR * 2;  // bytes per tile
     constexpr int KS = D / 16;
+    // MFMA steps by which LDS operand reads lead their use (registers permitting)
+    constexpr int KP = D == 128 ? 4 : 2;
+    // The step loops below must be unrolled (register arrays are indexed by the step).  At d = 256
+    // with the causal mask the unrolled body passes the size at which "#pragma unroll" gives up
+    // silently; this file is compiled with that threshold raised (see build.py).
     // S and dP contract over the whole head dimension; dK and dV are produced for a slice of DO
     // columns per workgroup (the whole of it up to d = 128; at d = 256 two workgroups, blockIdx.y,
     // take half each and both recompute S and dP -- the accumulators of all 256 columns, 256
@@ -82,11 +89,17 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     constexpr int DT = DO / 32;
     constexpr int CPR = D / 8;     // 16-byte chunks per row
     constexpr int QCH = BQ * CPR / NT;  // chunks per thread for a Q / dO tile
+    // With one wave per SIMD (more than 256 registers per lane) MFMA results land in the
+    // accumulation half of the register file unless told otherwise; the score tiles S and dP,
+    // which the exponentials read, are then produced by MfmaVgprAcc into ordinary registers.
+    constexpr bool VACC = D >= 128;
     using E = Elem<Tag>;
     const int col0 = blockIdx.y * DO;  // first column of this workgroup's slice
 
-    __shared__ __attribute__((aligned(16))) uint16_t lds_q[2][BQ * RSTR];
-    __shared__ __attribute__((aligned(16))) uint16_t lds_do[2][BQ * RSTR];
+    // tiles 0, 1: Q_i double-buffered; tiles 2, 3: dO_i (a fixed distance from the Q tile of the
+    // same parity, so one address register serves both)
+    __shared__ __attribute__((aligned(16))) uint16_t lds_t[4][BQ * RSTR];
+    constexpr int DO_DIST = 2 * TILE_B;
     __shared__ __attribute__((aligned(16))) float lds_l[2][BQ];
     __shared__ __attribute__((aligned(16))) float lds_d[2][BQ];
 
@@ -116,8 +129,8 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     }
     // The kernel needs more than 256 registers per lane, so part of them live in the accumulation
     // half of the register file, which only MFMA can address directly.  K_j / V_j operands and the
-    // dK / dV accumulators are touched by MFMA alone: pin the operands there so that the score
-    // tiles, which the exponentials read, stay in ordinary registers and need no copies.
+    // dK / dV accumulators are touched by MFMA alone and live there; the score tiles, which the
+    // exponentials read, are kept in ordinary registers (VACC below).
     if constexpr (D >= 128) {
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(kreg[ks]), "+a"(vreg[ks]));
@@ -155,38 +168,58 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     // buffer resources and read as zero.
     const __amdgpu_buffer_rsrc_t q_rsrc = make_buffer(qh, (uint32_t)N * D * 2);
     const __amdgpu_buffer_rsrc_t do_rsrc = make_buffer(doh, (uint32_t)N * D * 2);
-    i32x4 qpre[QCH], dopre[QCH];
+    // At d = 256 the staging registers of a whole tile pair (64 per lane) would not fit beside the
+    // operands and accumulators: the tile travels in two halves, the first stored to LDS between
+    // the two GEMM pairs of the iteration, the second at its end.
+    constexpr int NG = QCH >= 8 ? 2 : 1;
+    constexpr int QG = QCH / NG;
+    i32x4 qpre[QG], dopre[QG];
     float lpre = 0.f;  // threads 0..63 carry L, 64..127 carry D
-    auto load_tile = [&](int it) {
-        const int q0 = it * BQ;
+    int lrow = 0;
+    // The next tile travels global -> registers (issued at the top of an iteration) -> LDS (at its
+    // end).  Spreading the loads and the LDS writes over the MFMA steps was measured and is no
+    // faster: the single wave of a SIMD is bound by its own instruction issue, not by where in
+    // the iteration an instruction sits.
+    auto load_group = [&](int it, int grp) {  // chunks grp * QG .. of the Q_i and dO_i tiles
 #pragma unroll
-        for (int i = 0; i < QCH; ++i) {
-            qpre[i] = buffer_load_16B(q_rsrc, q0 * D * 2 + (tid + i * NT) * 16);
-            dopre[i] = buffer_load_16B(do_rsrc, q0 * D * 2 + (tid + i * NT) * 16);
-        }
-        if (tid < 2 * BQ) {
-            const int r = q0 + (tid & (BQ - 1));
-            const float* src = tid < BQ ? lh : dh;
-            float x = src[min(r, N - 1)];
-            // rows past N get L = +inf so that P = exp2(0 - inf) = 0, and D = 0
-            lpre = tid < BQ ? (r < N ? x * kLog2e : INFINITY) : (r < N ? x : 0.f);
+        for (int j = 0; j < QG; ++j) {
+            const int i = grp * QG + j;
+            qpre[j] = buffer_load_16B(q_rsrc, it * BQ * D * 2 + (tid + i * NT) * 16);
+            dopre[j] = buffer_load_16B(do_rsrc, it * BQ * D * 2 + (tid + i * NT) * 16);
         }
     };
-    auto store_tile = [&](int st) {
-#pragma unroll
-        for (int i = 0; i < QCH; ++i) {
-            int c = tid + i * NT;
-            int row = c / CPR, cc = c % CPR;
-            *reinterpret_cast<i32x4*>(lds_q[st] + row * RSTR + cc * 8) = qpre[i];
-            *reinterpret_cast<i32x4*>(lds_do[st] + row * RSTR + cc * 8) = dopre[i];
+    auto load_ld = [&](int it) {
+        if (tid < 2 * BQ) {
+            // the raw value only: anything computed from it here would make the wave wait for the
+            // load on the spot, once per iteration
+            lrow = it * BQ + (tid & (BQ - 1));
+            lpre = (tid < BQ ? lh : dh)[min(lrow, N - 1)];
         }
-        if (tid < BQ) lds_l[st][tid] = lpre;
-        else if (tid < 2 * BQ) lds_d[st][tid - BQ] = lpre;
+    };
+    auto store_group = [&](int st, int grp) {
+#pragma unroll
+        for (int j = 0; j < QG; ++j) {
+            int c = tid + (grp * QG + j) * NT;
+            int row = c / CPR, cc = c % CPR;
+            *reinterpret_cast<i32x4*>(lds_t[st] + row * RSTR + cc * 8) = qpre[j];
+            *reinterpret_cast<i32x4*>(lds_t[2 + st] + row * RSTR + cc * 8) = dopre[j];
+        }
+    };
+    auto store_ld = [&](int st) {
+        // rows past N get L = +inf so that P = exp2(0 - inf) = 0, and D = 0.  D is kept negated:
+        // the dP accumulators start from -D_i, so dP - D comes out of the MFMAs
+        if (tid < BQ) lds_l[st][tid] = lrow < N ? lpre * kLog2e : INFINITY;
+        else if (tid < 2 * BQ) lds_d[st][tid - BQ] = lrow < N ? -lpre : 0.f;
     };
 
     if (it0 < n_qtiles) {
-        load_tile(it0);
-        store_tile(0);
+        load_ld(it0);
+#pragma unroll
+        for (int grp = 0; grp < NG; ++grp) {
+            load_group(it0, grp);
+            store_group(0, grp);
+        }
+        store_ld(0);
     }
     __syncthreads();
 
@@ -194,7 +227,10 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         const int st = (it - it0) & 1;
         const int q0 = it * BQ;
         const bool more = it + 1 < n_qtiles;
-        if (more) load_tile(it + 1);
+        if (more) {
+            load_group(it + 1, 0);
+            load_ld(it + 1);
+        }
 
         // One wave per SIMD: nothing but this wave's own instruction stream can keep the matrix
         // pipe busy while the exponentials run.  The iteration is therefore software-pipelined by
@@ -205,20 +241,44 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         //   stage 3: dV, dK += sub-tile 0 ||  P, dS of sub-tile 1
         //   stage 4: dV, dK += sub-tile 1                     (MFMA only)
         // Every step ends in a full scheduling barrier so the interleaving below is what runs, and
-        // LDS operand reads lead their MFMAs by kPipe steps.
+        // LDS operand reads lead their MFMAs by KP steps.
         auto body = [&](auto mask_tag) {
             constexpr bool MASK = decltype(mask_tag)::value;
             const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
             i32x4 pa[2][2], dsa[2][2];  // [sub-tile][16-query slab]: P^T and dS^T as A operands
             f32x16 sacc[2], pacc[2];
 
-            // L (log2 units) and D of the lane's query rows, fetched four rows at a time one step
-            // before they are needed so that few of them are live at once
-            f32x4 l4[2][4], d4[2][4];
-            auto fetch_ld = [&](int sub, int g) {
-                const int ql = sub * 32 + 8 * g + 4 * half;  // first of 4 consecutive query rows
-                l4[sub][g] = *reinterpret_cast<const f32x4*>(&lds_l[st][ql]);
-                d4[sub][g] = *reinterpret_cast<const f32x4*>(&lds_d[st][ql]);
+            // This tile's LDS addresses, one register each; every read below adds a compile-time
+            // offset that fits the instruction's immediate field.
+            // Row reads: lane (col, half) takes 8 elements from 16 ks + 8 half of row col (+ 32 per
+            // sub-tile).  Transposing reads: lane takes 4 elements at tr_col of row 4 half + tr_row
+            // (+ 8 for the second read, + 16 per slab), 32 elements further per d-tile.
+            uint32_t q_rows = lds_address(lds_t[st]) + (col * RSTR + half * 8) * 2;
+            uint32_t q_tr = lds_address(lds_t[st]) + ((4 * half + tr_row) * RSTR + tr_col + col0) * 2;
+            uint32_t l_rows = lds_address(lds_l[st]) + 16 * half;  // 4 consecutive rows from 4 * half
+            uint32_t d_rows = lds_address(lds_d[st]) + 16 * half;
+            asm volatile("" : "+v"(q_rows), "+v"(q_tr), "+v"(l_rows), "+v"(d_rows));
+            auto row_addr = [&](int u) -> uint32_t {  // step u = (sub-tile, ks) of stages 1 and 2
+                const int sub = u / KS, ks = u % KS;
+                return q_rows + (sub * 32 * RSTR + ks * 16) * 2;
+            };
+            auto tr_addr = [&](int u, int hi) -> uint32_t {  // step u = (16-query slab, d-tile) of stages 3 and 4
+                const int slab = u / DT, dt = u % DT;
+                return q_tr + ((slab * 16 + hi * 8) * RSTR + dt * 32) * 2;
+            };
+
+            // L (log2 units) of the lane's query rows, fetched four rows at a time one step before
+            // they are needed so that few of them are live at once
+            f32x4 l4[2][4];
+            auto fetch_l = [&](int sub, int g) { l4[sub][g] = lds_load_4f(l_rows + (sub * 32 + 8 * g) * 4); };
+            // dP starts from -D_i: accumulator registers 4g..4g+3 are query rows 8g+4*half..+3
+            auto init_dp = [&](int sub) {
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    f32x4 t = lds_load_4f(d_rows + (sub * 32 + 8 * g) * 4);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) pacc[sub][4 * g + r] = t[r];
+                }
             };
 
             // elements 2c, 2c+1 of a sub-tile: P, dS and one packed register of each
@@ -234,7 +294,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                         p = masked ? 0.f : p;
                     }
                     pv[e] = p;
-                    dsv[e] = p * (pacc[sub][rr] - d4[sub][g][r]);
+                    dsv[e] = p * pacc[sub][rr];
                 }
                 pa[sub][c >> 2][c & 3] = E::pack2(pv[0], pv[1]);
                 dsa[sub][c >> 2][c & 3] = E::pack2(dsv[0], dsv[1]);
@@ -243,34 +303,43 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
             // ---- stages 1 and 2: S = Q_i K_j^T, dP = dO_i V_j^T
             {
                 constexpr int NU = 2 * KS;
-                const uint16_t* qrow = lds_q[st] + col * RSTR + half * 8;
-                const uint16_t* dorow = lds_do[st] + col * RSTR + half * 8;
-                i32x4 aq[kPipe], ado[kPipe];
+                i32x4 aq[KP], ado[KP];
 #pragma unroll
-                for (int u = 0; u < kPipe; ++u) {
-                    aq[u] = *reinterpret_cast<const i32x4*>(qrow + (u / KS) * 32 * RSTR + (u % KS) * 16);
-                    ado[u] = *reinterpret_cast<const i32x4*>(dorow + (u / KS) * 32 * RSTR + (u % KS) * 16);
+                for (int u = 0; u < KP; ++u) {
+                    aq[u] = lds_load_16B(row_addr(u));
+                    ado[u] = lds_load_16B(row_addr(u) + DO_DIST);
                 }
+                init_dp(0);
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
                     const int sub = u / KS, ks = u % KS;
-                    i32x4 a0 = aq[u % kPipe], a1 = ado[u % kPipe];
-                    if (u + kPipe < NU) {
-                        const int v = u + kPipe;
-                        aq[u % kPipe] = *reinterpret_cast<const i32x4*>(qrow + (v / KS) * 32 * RSTR + (v % KS) * 16);
-                        ado[u % kPipe] = *reinterpret_cast<const i32x4*>(dorow + (v / KS) * 32 * RSTR + (v % KS) * 16);
+                    i32x4 a0 = aq[u % KP], a1 = ado[u % KP];
+                    if (u + KP < NU) {
+                        aq[u % KP] = lds_load_16B(row_addr(u + KP));
+                        ado[u % KP] = lds_load_16B(row_addr(u + KP) + DO_DIST);
                     }
-                    sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
-                    pacc[sub] = E::mma(a1, vreg[ks], ks == 0 ? zero : pacc[sub]);
-                    if (sub == 0 && ks == KS - 1) fetch_ld(0, 0);
+                    if (u == KS - 2) init_dp(1);
+                    if constexpr (VACC) {
+                        if (ks == 0) MfmaVgprAcc<Tag>::first(sacc[sub], a0, kreg[ks]);
+                        else MfmaVgprAcc<Tag>::run(sacc[sub], a0, kreg[ks]);
+                        MfmaVgprAcc<Tag>::run(pacc[sub], a1, vreg[ks]);
+                    } else {
+                        sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
+                        pacc[sub] = E::mma(a1, vreg[ks], pacc[sub]);
+                    }
+                    if (sub == 0 && ks == KS - 1) fetch_l(0, 0);
                     if (sub == 1) {
-                        // the 8 register pairs of sub-tile 0 spread over the KS steps; the L, D group
+                        // sub-tile 0's results were written by MFMAs the hazard checker cannot see
+                        if constexpr (VACC) {
+                            if (ks == 0) mfma_result_wait(sacc[0], pacc[0]);
+                        }
+                        // the 8 register pairs of sub-tile 0 spread over the KS steps; the L group
                         // of a pair is fetched one step before the step that needs it first
                         // pair c runs at step c KS / 8
 #pragma unroll
                         for (int g = 1; g < 4; ++g)
-                            if ((2 * g * KS) / 8 == ks + 1) fetch_ld(0, g);
-                        if (ks == KS - 1) fetch_ld(1, 0);
+                            if ((2 * g * KS) / 8 == ks + 1) fetch_l(0, g);
+                        if (ks == KS - 1) fetch_l(1, 0);
 #pragma unroll
                         for (int c = 0; c < 8; ++c)
                             if ((c * KS) / 8 == ks) softmax_pair(0, c);
@@ -279,38 +348,46 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                 }
             }
 
+            if constexpr (NG == 2) {
+                if (more) {  // the other LDS buffers are free for the whole iteration
+                    store_group(st ^ 1, 0);
+                    load_group(it + 1, 1);
+                }
+            }
+
             // ---- stages 3 and 4: dV_j += P^T dO_i, dK_j += dS^T Q_i (contract over the tile's queries)
             {
                 constexpr int NU = 2 * 2 * DT;  // (sub, slab, d-tile)
-                const int rbase = (4 * half + tr_row) * RSTR + tr_col;
-                auto off = [&](int u) { return rbase + ((u / DT) * 16) * RSTR + col0 + (u % DT) * 32; };
-                i32x2 dlo[kPipe], dhi[kPipe], qlo[kPipe], qhi[kPipe];
+                i32x2 dlo[KP], dhi[KP], qlo[KP], qhi[KP];
 #pragma unroll
-                for (int u = 0; u < kPipe; ++u) {
-                    dlo[u] = lds_read_tr16(lds_do[st] + off(u));
-                    dhi[u] = lds_read_tr16(lds_do[st] + off(u) + 8 * RSTR);
-                    qlo[u] = lds_read_tr16(lds_q[st] + off(u));
-                    qhi[u] = lds_read_tr16(lds_q[st] + off(u) + 8 * RSTR);
+                for (int u = 0; u < KP; ++u) {
+                    dlo[u] = lds_read_tr16(tr_addr(u, 0) + DO_DIST);
+                    dhi[u] = lds_read_tr16(tr_addr(u, 1) + DO_DIST);
+                    qlo[u] = lds_read_tr16(tr_addr(u, 0));
+                    qhi[u] = lds_read_tr16(tr_addr(u, 1));
                 }
 #pragma unroll
                 for (int u = 0; u < NU; ++u) {
                     const int sub = u / (2 * DT), s2 = (u / DT) % 2, dt = u % DT;
-                    const int w = u % kPipe;
+                    const int w = u % KP;
                     i32x4 b = {dlo[w][0], dlo[w][1], dhi[w][0], dhi[w][1]};
                     i32x4 b2 = {qlo[w][0], qlo[w][1], qhi[w][0], qhi[w][1]};
-                    if (u + kPipe < NU) {
-                        dlo[w] = lds_read_tr16(lds_do[st] + off(u + kPipe));
-                        dhi[w] = lds_read_tr16(lds_do[st] + off(u + kPipe) + 8 * RSTR);
-                        qlo[w] = lds_read_tr16(lds_q[st] + off(u + kPipe));
-                        qhi[w] = lds_read_tr16(lds_q[st] + off(u + kPipe) + 8 * RSTR);
+                    if (u + KP < NU) {
+                        dlo[w] = lds_read_tr16(tr_addr(u + KP, 0) + DO_DIST);
+                        dhi[w] = lds_read_tr16(tr_addr(u + KP, 1) + DO_DIST);
+                        qlo[w] = lds_read_tr16(tr_addr(u + KP, 0));
+                        qhi[w] = lds_read_tr16(tr_addr(u + KP, 1));
                     }
                     dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
                     dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
                     if (sub == 0) {
+                        if constexpr (VACC) {
+                            if (u == 0) mfma_result_wait(sacc[1], pacc[1]);
+                        }
                         constexpr int PP = 8 / (2 * DT);
 #pragma unroll
                         for (int g = 1; g < 4; ++g)
-                            if ((2 * g) / PP == u + 1) fetch_ld(1, g);
+                            if ((2 * g) / PP == u + 1) fetch_l(1, g);
 #pragma unroll
                         for (int p = 0; p < PP; ++p) softmax_pair(1, u * PP + p);
                     }
@@ -320,7 +397,10 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
         };
         body(mask_tag);
 
-        if (more) store_tile(st ^ 1);
+        if (more) {
+            store_group(st ^ 1, NG - 1);
+            store_ld(st ^ 1);
+        }
         __syncthreads();
     };
     int it = it0;

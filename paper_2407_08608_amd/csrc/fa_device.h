@@ -12,6 +12,8 @@
 // register permutation of the paper's section 3.3 (FP8 layout discussion).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 #include <stdint.h>
 
 namespace fa {
@@ -65,12 +67,58 @@ template <> struct Elem<f16_tag> {
     }
 };
 
+// The same MFMA written as inline assembly, to choose the half of the register file each operand
+// lives in.  A kernel that needs more than 256 registers per lane gets MFMA results in the
+// accumulation half by default, where no VALU instruction can read them: a score tile that the
+// softmax reads would pay one copy per element.  Here the accumulator is forced into ordinary
+// registers and the B operand (touched by MFMA alone) is taken from the accumulation half.
+// The compiler's hazard checker cannot see inside: a VALU read of the accumulator must be
+// separated from the MFMA that wrote it by mfma_result_wait().
+template <typename Tag> struct MfmaVgprAcc;
+#define FA_DEFINE_MFMA_VGPR_ACC(TAG, OPCODE)                                                          \
+    template <> struct MfmaVgprAcc<TAG> {                                                             \
+        static __device__ __forceinline__ void run(f32x16& acc, const i32x4& a, const i32x4& b) {     \
+            asm volatile(OPCODE " %0, %1, %2, %0" : "+v"(acc) : "v"(a), "a"(b));                      \
+        }                                                                                             \
+        static __device__ __forceinline__ void first(f32x16& acc, const i32x4& a, const i32x4& b) {   \
+            asm volatile(OPCODE " %0, %1, %2, 0" : "=&v"(acc) : "v"(a), "a"(b));                      \
+        }                                                                                             \
+    };
+FA_DEFINE_MFMA_VGPR_ACC(bf16_tag, "v_mfma_f32_32x32x16_bf16")
+FA_DEFINE_MFMA_VGPR_ACC(f16_tag, "v_mfma_f32_32x32x16_f16")
+#undef FA_DEFINE_MFMA_VGPR_ACC
+
+// 24 wait states (the 8-pass MFMA needs 11 between its issue and a VALU read of its result).  The
+// accumulators are operands of the statement, so no reader can be scheduled above it; placed
+// after independent MFMAs the wait costs nothing, the matrix pipe is busy meanwhile.
+static __device__ __forceinline__ void mfma_result_wait(f32x16& x, f32x16& y) {
+    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(x), "+v"(y));
+}
+
+// 32-bit LDS byte address of a __shared__ object, and loads through such an address: a base kept
+// in one register with compile-time offsets lets every read use the instruction's immediate
+// offset field instead of an address computation of its own.
+static __device__ __forceinline__ uint32_t lds_address(const void* p) { return (uint32_t)(uintptr_t)p; }
+static __device__ __forceinline__ i32x4 lds_load_16B(uint32_t addr) {
+    typedef i32x4 __attribute__((address_space(3))) * lds_vec_ptr;
+    return *(lds_vec_ptr)(uintptr_t)addr;
+}
+static __device__ __forceinline__ f32x4 lds_load_4f(uint32_t addr) {
+    typedef f32x4 __attribute__((address_space(3))) * lds_vec_ptr;
+    return *(lds_vec_ptr)(uintptr_t)addr;
+}
+
 // ds_read_b64_tr_b16: the 16 lanes of a group each point at 4 consecutive 16-bit elements;
 // seen as a 4x16 matrix (row r = what lanes 4r..4r+3 point at), lane i of the group
 // receives column i.  Used to read a [key][d] tile as the key-contiguous MFMA operand.
 static __device__ __forceinline__ i32x2 lds_read_tr16(const void* lds_ptr) {
     typedef s16x4 __attribute__((address_space(3))) * lds_vec_ptr;
     s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_vec_ptr)(uintptr_t)lds_ptr);
+    return __builtin_bit_cast(i32x2, v);
+}
+static __device__ __forceinline__ i32x2 lds_read_tr16(uint32_t lds_addr) {
+    typedef s16x4 __attribute__((address_space(3))) * lds_vec_ptr;
+    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_vec_ptr)(uintptr_t)lds_addr);
     return __builtin_bit_cast(i32x2, v);
 }
 

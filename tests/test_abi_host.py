@@ -97,3 +97,20 @@ def test_flop_accounting_matches_the_papers_ablation_table():
     # matmul FLOPs per exponential at head dim 128: 4*N^2*d / N^2 = 512
     e = g["exp_vs_matmul"]
     assert binding.attention_flops(1, 1, 64, e["hdim"], False) / (64 * 64) == e["matmul_flops_per_exp"]
+
+
+def test_mfma_hazard_checker_finds_planted_early_access():
+    """The build runs this checker over the backward kernels' assembly; here it is shown to see what
+    it is for, on a listing written by hand."""
+    from paper_2407_08608_amd import mfma_hazard_check as hz
+    head = "_Z6kernelv:\n\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], a[0:3], 0\n\t;;#ASMEND\n"
+    chain = "\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[4:7], a[4:7], v[16:31]\n\t;;#ASMEND\n"
+    wait = "\ts_nop 15\n\ts_nop 7\n"
+    read = "\tv_exp_f32_e32 v40, v17\n"
+    assert hz.check(head + chain + wait + read) == []
+    assert len(hz.check(head + chain + read)) == 1                       # VALU read right behind the MFMA
+    assert len(hz.check(head + "\tv_mov_b32_e32 v50, v31\n" + chain + wait + read)) == 1   # a copy between two MFMAs
+    assert len(hz.check(head + "\tds_read_b128 v[28:31], v60\n" + wait)) == 1              # overwritten too early
+    assert len(hz.check(head + "\ts_nop 7\n\tv_mfma_f32_32x32x16_bf16 a[0:15], v[16:19], v[8:11], a[0:15]\n")) == 1
+    # an MFMA the compiler scheduled itself (no ASMSTART) is the compiler's business
+    assert hz.check("_Z6kernelv:\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], 0\n" + read) == []
