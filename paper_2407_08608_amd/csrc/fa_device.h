@@ -88,12 +88,14 @@ FA_DEFINE_MFMA_VGPR_ACC(bf16_tag, "v_mfma_f32_32x32x16_bf16")
 FA_DEFINE_MFMA_VGPR_ACC(f16_tag, "v_mfma_f32_32x32x16_f16")
 #undef FA_DEFINE_MFMA_VGPR_ACC
 
-// 24 wait states (the 8-pass MFMA needs 11 between its issue and a VALU read of its result).  The
-// accumulators are operands of the statement, so no reader can be scheduled above it; placed
-// after independent MFMAs the wait costs nothing, the matrix pipe is busy meanwhile.
+// 13 wait states: the 8-pass MFMA needs 11 between its issue and a VALU read of its result, and
+// the compiler leaves 12 or more in the code it schedules itself.  The accumulators are operands
+// of the statement, so no reader can be scheduled above it; placed after an independent MFMA
+// most of the wait passes while the matrix pipe works on that one.
 static __device__ __forceinline__ void mfma_result_wait(f32x16& x, f32x16& y) {
-    asm volatile("s_nop 15\n\ts_nop 7" : "+v"(x), "+v"(y));
+    asm volatile("s_nop 12" : "+v"(x), "+v"(y));
 }
+static __device__ __forceinline__ void mfma_result_wait(f32x16& x) { asm volatile("s_nop 12" : "+v"(x)); }
 
 // 32-bit LDS byte address of a __shared__ object, and loads through such an address: a base kept
 // in one register with compile-time offsets lets every read use the instruction's immediate

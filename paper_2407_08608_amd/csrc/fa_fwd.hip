@@ -313,6 +313,277 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 }
 
 // ---------------------------------------------------------------------------------------
+// Head dimension 256: four waves, one per SIMD.
+//
+// The output accumulator of 32 query rows (128 registers per lane) and the 64 registers of Q_i
+// leave room for one wave per SIMD, so nothing but the wave's own instruction stream can keep
+// the matrix pipe busy while the exponentials run.  The loop is therefore software-pipelined
+// across key blocks the way the paper's Algorithm 2 (section 3.2) pipelines within a warpgroup:
+// the scores of block t+1 are produced while the exponentials of block t run,
+//   stage A: S(t+1)^T = K(t+1) Q^T     ||  reference maximum for S(t) (raised lazily; rarely a rescale
+//                                          of O and l), P~(t) = exp2(S(t) - m), row sums
+//   stage B: O^T += V(t)^T P~(t)^T     ||  mask and row maxima of S(t+1)
+// so both score tiles are live at once (the paper's extra S_next registers), K runs one block
+// ahead of V through the LDS buffers, and the only rescale of O sits at the head of stage A,
+// whose MFMAs do not touch O.  O and Q live in the accumulation half of the register file, which MFMA
+// alone can address; the score tiles are produced by MfmaVgprAcc into ordinary registers, where
+// the softmax reads them without a copy per score.  Every step ends in a full scheduling
+// barrier, so the interleaving written here is what runs, and LDS operand reads lead their
+// MFMAs by KP steps.  The block after the last one is computed like any other and comes out
+// fully masked, which is why shorter problems stay on fa_fwd_16bit_kernel.
+template <typename Tag, bool CAUSAL>
+__global__ void __launch_bounds__(256, 1)
+fa_fwd_d256_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+                   uint16_t* __restrict__ o, float* __restrict__ lse, int N, int n_qtiles, int total_wg,
+                   int kv_group, float scale) {
+    constexpr int D = 256, BC = 64, NT = 256, BR = 128;
+    constexpr int KSTR = D + 8;   // +16 B per row: 128-bit row reads hit distinct banks
+    constexpr int VSTR = D + 32;  // +64 B per row: the 4-row transposing reads hit distinct banks
+    constexpr int KS = D / 16, DT = D / 32, KP = 4;
+    using E = Elem<Tag>;
+    using Copy = TileCopy<D, BC, NT>;
+
+    __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][BC * KSTR];
+    __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][BC * VSTR];
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+
+    // work items as in fa_fwd_16bit_kernel: causal tiles i and n_qtiles-1-i form one item
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const size_t kv_off = (size_t)(bh / kv_group) * N * D;
+    const uint16_t* qh = q + head_off;
+    const float sc = scale * kLog2e;
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_buffer(k + kv_off, (uint32_t)N * D * 2);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_buffer(v + kv_off, (uint32_t)N * D * 2);
+    const int tr_row = (lane & 15) >> 2;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;  // the longer tile first
+    const int wave_q0 = qt * BR + wave * 32;
+    const int limit = CAUSAL ? min(wave_q0 + col, N - 1) : N - 1;  // last key this lane's query sees
+
+    // Q_i^T as the B operand of S^T = K Q^T, resident for the whole loop
+    i32x4 qreg[KS];
+    {
+        const int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+            qreg[ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
+    }
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f, mb = 0.f;
+
+    const int last_q = min(qt * BR + BR, N) - 1;
+    const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+
+    // ---- pieces shared by the prologue and the loop
+    float mxp[4];
+    auto need_mask = [&](int t) { return (t * BC + BC > N) || (CAUSAL && t * BC + BC - 1 > wave_q0); };
+    auto mask_block = [&](int t, f32x16 (&s)[2]) {  // keys past N, and keys after the query when causal
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = t * BC + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                if (key > limit) s[kt][r] = -INFINITY;
+            }
+    };
+    auto max_part = [&](f32x16 (&s)[2], int part) {  // registers 8 part .. 8 part + 7 of the 32
+#pragma unroll
+        for (int i = 8 * part; i < 8 * part + 8; ++i)
+            mxp[i & 3] = i < 4 ? s[0][i] : fmaxf(mxp[i & 3], s[i >> 4][i & 15]);
+    };
+    // K rows for S^T (A operand), 32 steps (kt, ks); the scores land in ordinary registers
+    auto score_step = [&](f32x16 (&s)[2], uint32_t k_rows, i32x4 (&abuf)[KP], int u) {
+        constexpr int NU = 2 * KS;
+        const int kt = u / KS, ks = u % KS;
+        const i32x4 a = abuf[u % KP];
+        if (u + KP < NU) {
+            const int w = u + KP;
+            abuf[u % KP] = lds_load_16B(k_rows + ((w / KS) * 32 * KSTR + (w % KS) * 16) * 2);
+        }
+        if (ks == 0) MfmaVgprAcc<Tag>::first(s[kt], a, qreg[ks]);
+        else MfmaVgprAcc<Tag>::run(s[kt], a, qreg[ks]);
+    };
+    auto score_prefetch = [&](uint32_t k_rows, i32x4 (&abuf)[KP]) {
+#pragma unroll
+        for (int u = 0; u < KP; ++u) abuf[u] = lds_load_16B(k_rows + ((u / KS) * 32 * KSTR + (u % KS) * 16) * 2);
+    };
+
+    // Staging, global -> registers -> LDS, one 16-byte chunk per thread at a time.  A block's K and V
+    // are 64 KiB, half of what the CU's vector memory path moves in the time of the block's MFMAs:
+    // issued in one burst the loads make every wave sit in its own issue for over a thousand
+    // cycles.  They are spread over the MFMA steps instead, one chunk every CH_EVERY steps, and
+    // each chunk is written to the LDS a stage later, when it has long arrived:
+    //   stage A of block t: load K(t+2) chunks          | write the V(t+1) chunks loaded in block t-1
+    //   stage B of block t: write those K(t+2) chunks   | load V(t+2) chunks
+    // (K(t+2) replaces K(t), last read in block t-1; V(t+1) replaces V(t-1), last read in block t-1;
+    // both become visible at the barrier that ends block t.)  Blocks past the end read as zero.
+    constexpr int NCH = Copy::kPerThread, CH_EVERY = 2 * KS / NCH;
+    static_assert(NCH * CH_EVERY == 2 * KS && 4 * DT == 2 * KS, "one chunk every CH_EVERY steps of either stage");
+    i32x4 kpre[NCH], vpre[NCH];
+    auto load_chunk = [&](__amdgpu_buffer_rsrc_t rsrc, int block_idx, int i) {
+        return buffer_load_16B(rsrc, block_idx * BC * D * 2 + (tid + i * NT) * 16);
+    };
+    auto store_chunk = [&](uint16_t* lds, int stride, int i, const i32x4& x) {
+        const int c = tid + i * NT;
+        *reinterpret_cast<i32x4*>(lds + (c / (D / 8)) * stride + (c % (D / 8)) * 8) = x;
+    };
+    Copy::from_global(k_rsrc, 0, tid, kpre);
+    Copy::from_global(v_rsrc, 0, tid, vpre);
+    Copy::template to_lds<KSTR>(lds_k[0], tid, kpre);
+    Copy::template to_lds<VSTR>(lds_v[0], tid, vpre);
+    Copy::from_global(k_rsrc, BC * D * 2, tid, kpre);  // K(1)
+    Copy::from_global(v_rsrc, BC * D * 2, tid, vpre);  // V(1), written to the LDS during block 0
+    // the Q loads complete here and Q moves to the accumulation half
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qreg[ks]));
+    __syncthreads();
+
+    // ---- prologue: S(0) and its reference maximum (O and l are still zero: nothing to rescale)
+    f32x16 sa[2], sb[2];
+    {
+        uint32_t k_rows = lds_address(lds_k[0]) + (col * KSTR + half * 8) * 2;
+        asm volatile("" : "+v"(k_rows));
+        i32x4 abuf[KP];
+        score_prefetch(k_rows, abuf);
+#pragma unroll
+        for (int u = 0; u < 2 * KS; ++u) {
+            score_step(sa, k_rows, abuf, u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        Copy::template to_lds<KSTR>(lds_k[1], tid, kpre);
+        mfma_result_wait(sa[0], sa[1]);
+        if (need_mask(0)) mask_block(0, sa);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) max_part(sa, part);
+        m_run = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])));
+        mb = m_run * sc;
+    }
+    __syncthreads();
+
+    // ---- one key block: `cur` holds S(t), `nxt` receives S(t+1)
+    auto block = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+        i32x4 pb[4];  // P~(t)^T as B operands, 16 keys each
+        float psum = 0.f;
+        uint32_t k_rows = lds_address(lds_k[(t + 1) & 1]) + (col * KSTR + half * 8) * 2;
+        uint32_t v_tr = lds_address(lds_v[t & 1]) + ((4 * half + tr_row) * VSTR + tr_col) * 2;
+        asm volatile("" : "+v"(k_rows), "+v"(v_tr));
+
+        // ---- stage A
+        {
+            i32x4 abuf[KP];
+            score_prefetch(k_rows, abuf);
+#pragma unroll
+            for (int u = 0; u < 2 * KS; ++u) {
+                score_step(nxt, k_rows, abuf, u);
+                if (u % CH_EVERY == 0) {
+                    store_chunk(lds_v[(t + 1) & 1], VSTR, u / CH_EVERY, vpre[u / CH_EVERY]);
+                    kpre[u / CH_EVERY] = load_chunk(k_rsrc, t + 2, u / CH_EVERY);
+                }
+                if (u == 0) {
+                    // Reference maximum for S(t) from the row maxima taken beside the previous block's
+                    // products: raised only when they exceed it by more than 2^kLazyLog2 (P~ <= 2^kLazyLog2
+                    // otherwise and the factor cancels in O / l).  Every product of the previous block has
+                    // been issued, and the MFMAs of this stage write the score registers only, so the rare
+                    // rescale of O is in order here.  (Block 0: the prologue has set the reference; no rise.)
+                    const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])));
+                    const bool raise = (mx - m_run) * sc > kLazyLog2;
+                    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                        const float corr = raise ? fast_exp2((m_run - mx) * sc) : 1.0f;
+                        m_run = raise ? mx : m_run;
+                        l_run *= corr;
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[dt][r] *= corr;
+                    }
+                    mb = m_run * sc;
+                }
+#pragma unroll
+                for (int c = 0; c < 16; ++c)
+                    if (2 + (c * 30) / 16 == u) {  // pair c of the 16: two scores of S(t) become one packed register of P~
+                        const int kt = c / 8, j = c % 8;
+                        const float p0 = fast_exp2(__builtin_fmaf(cur[kt][2 * j], sc, -mb));
+                        const float p1 = fast_exp2(__builtin_fmaf(cur[kt][2 * j + 1], sc, -mb));
+                        psum += p0 + p1;
+                        pb[2 * kt + (j >> 2)][j & 3] = E::pack2(p0, p1);
+                    }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            l_run += psum;
+        }
+
+        // ---- stage B
+        {
+            constexpr int NU = 4 * DT;  // (16-key slab, d-tile)
+            auto v_addr = [&](int u, int hi) -> uint32_t {
+                return v_tr + (((u / DT) * 16 + hi * 8) * VSTR + (u % DT) * 32) * 2;
+            };
+            i32x2 lo[KP], hi[KP];
+#pragma unroll
+            for (int u = 0; u < KP; ++u) {
+                lo[u] = lds_read_tr16(v_addr(u, 0));
+                hi[u] = lds_read_tr16(v_addr(u, 1));
+            }
+            const bool mask_next = need_mask(t + 1);
+#pragma unroll
+            for (int u = 0; u < NU; ++u) {
+                const int sl = u / DT, dt = u % DT;
+                const i32x4 a = {lo[u % KP][0], lo[u % KP][1], hi[u % KP][0], hi[u % KP][1]};
+                if (u + KP < NU) {
+                    lo[u % KP] = lds_read_tr16(v_addr(u + KP, 0));
+                    hi[u % KP] = lds_read_tr16(v_addr(u + KP, 1));
+                }
+                oacc[dt] = E::mma(a, pb[sl], oacc[dt]);
+                if (u == 0) mfma_result_wait(nxt[0], nxt[1]);  // written by MFMAs the hazard checker cannot see
+                if (u == 1 && mask_next) mask_block(t + 1, nxt);
+                if (u >= 2 && u < 6) max_part(nxt, u - 2);
+                if (u % CH_EVERY == 0) {
+                    store_chunk(lds_k[t & 1], KSTR, u / CH_EVERY, kpre[u / CH_EVERY]);
+                    vpre[u / CH_EVERY] = load_chunk(v_rsrc, t + 2, u / CH_EVERY);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+
+        __syncthreads();
+    };
+
+    for (int t = 0; t < n_blocks; t += 2) {
+        block(t, sa, sb);
+        if (t + 1 < n_blocks) block(t + 1, sb, sa);
+    }
+
+    // ---- epilogue: O / l, L = m + log l, through a 4 KiB LDS patch per wave (the last barrier of
+    // the loop has passed, so the K buffers are free)
+    {
+        char* patch = reinterpret_cast<char*>(&lds_k[0][0]) + wave * 4096;
+        static_assert(sizeof(lds_k) >= 4 * 4096, "patches must fit");
+        const int qi = wave_q0 + col;
+        const float l = sum_both_halves(l_run);
+        store_rows_via_lds<Tag, DT>(oacc, 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2), wave_q0, lane);
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
+    }
+    if (pass + 1 < n_pass) __syncthreads();  // the next pass's first tile overwrites the patches
+    }  // passes of a causal pair
+}
+
+// ---------------------------------------------------------------------------------------
 // Eight-wave ping-pong variant (head dimension 128).
 //
 // An eight-wave workgroup puts two waves on every SIMD (waves w and w + 4).  If all of them run
@@ -751,6 +1022,27 @@ static int launch_pingpong(const void* q, const void* k, const void* v, void* o,
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
+template <typename Tag>
+static int launch_d256(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
+                       float scale, int causal, hipStream_t stream) {
+    constexpr int BR = 128;
+    int n_qtiles = (N + BR - 1) / BR;
+    long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(256);
+    auto qp = static_cast<const uint16_t*>(q);
+    auto kp = static_cast<const uint16_t*>(k);
+    auto vp = static_cast<const uint16_t*>(v);
+    auto op = static_cast<uint16_t*>(o);
+    if (causal)
+        hipLaunchKernelGGL((fa_fwd_d256_kernel<Tag, true>), grid, block, 0, stream, qp, kp, vp, op, lse, N, n_qtiles,
+                           (int)total, H / H_kv, scale);
+    else
+        hipLaunchKernelGGL((fa_fwd_d256_kernel<Tag, false>), grid, block, 0, stream, qp, kp, vp, op, lse, N, n_qtiles,
+                           (int)total, H / H_kv, scale);
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
 // Kernel choice (measured on MI355X at the 16k-token benchmark shapes):
 //   d = 128: the eight-wave ping-pong kernel above 512 keys (causal tiles are paired into items
 //     of equal length there, so its coarser tiles cost no balance); shorter problems keep 128-row
@@ -782,7 +1074,12 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
         case 128:
             if (N <= 512) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256: return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case 256:
+#ifdef FA_D256_OLD
+            return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+#else
+            return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+#endif
         default: return FA_ERR_UNSUPPORTED;
     }
 }

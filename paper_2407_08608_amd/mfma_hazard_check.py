@@ -14,9 +14,8 @@ instruction that names a register of that range, and any MFMA that takes it as a
 before `need` wait states have passed.  A following MFMA that accumulates into exactly the same
 range is the hardware-interlocked case and is allowed.
 
-The 8-pass 32x32x16 MFMA needs 11 wait states before a VALU read of its result (the compiler
-leaves 12 or more in the code it schedules itself); `need` defaults to 19, the figure for a
-16-pass MFMA, for margin.
+The 8-pass 32x32x16 MFMA needs 11 wait states before a VALU read of its result; the compiler
+leaves 12 or more in the code it schedules itself, and `need` defaults to that.
 """
 import re
 import sys
@@ -34,7 +33,7 @@ def _vgprs(text):
     return out
 
 
-def check(asm_text, need=19, horizon=64):
+def check(asm_text, need=12, horizon=64):
     """Returns a list of (function, line number within the function, instruction, wait states so far)."""
     problems = []
     func, in_asm, pending, ln = None, False, [], 0

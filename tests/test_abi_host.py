@@ -105,7 +105,7 @@ def test_mfma_hazard_checker_finds_planted_early_access():
     from paper_2407_08608_amd import mfma_hazard_check as hz
     head = "_Z6kernelv:\n\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], a[0:3], 0\n\t;;#ASMEND\n"
     chain = "\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[4:7], a[4:7], v[16:31]\n\t;;#ASMEND\n"
-    wait = "\ts_nop 15\n\ts_nop 7\n"
+    wait = "\ts_nop 12\n"
     read = "\tv_exp_f32_e32 v40, v17\n"
     assert hz.check(head + chain + wait + read) == []
     assert len(hz.check(head + chain + read)) == 1                       # VALU read right behind the MFMA
