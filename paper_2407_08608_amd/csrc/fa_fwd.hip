@@ -330,7 +330,7 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 // the softmax reads them without a copy per score.  Every step ends in a full scheduling
 // barrier, so the interleaving written here is what runs, and LDS operand reads lead their
 // MFMAs by KP steps.  The block after the last one is computed like any other and comes out
-// fully masked, which is why shorter problems stay on fa_fwd_16bit_kernel.
+// fully masked (32 MFMAs per tile that add nothing).
 template <typename Tag, bool CAUSAL>
 __global__ void __launch_bounds__(256, 1)
 fa_fwd_d256_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -1049,8 +1049,8 @@ static int launch_d256(const void* q, const void* k, const void* v, void* o, flo
 //     workgroups of four waves, which fill the chip better.
 //   d = 64: eight waves share each K/V block (256 query rows per workgroup, two waves per SIMD),
 //     four waves for short problems.
-//   d = 256: the 128-register output accumulator allows only one wave per SIMD, so the operand
-//     reads are software-pipelined eight MFMA steps ahead instead.
+//   d = 256: the 128-register output accumulator allows only one wave per SIMD; fa_fwd_d256_kernel
+//     pipelines the softmax of one block under the score MFMAs of the next inside that wave.
 template <typename Tag>
 static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                           int d, float scale, int causal, int schedule, hipStream_t stream) {
@@ -1074,12 +1074,7 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
         case 128:
             if (N <= 512) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256:
-#ifdef FA_D256_OLD
-            return launch_16bit<Tag, 256, 64, 4, 1, 8>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-#else
-            return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-#endif
+        case 256: return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }

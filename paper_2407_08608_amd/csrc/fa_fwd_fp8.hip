@@ -270,6 +270,320 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
     }  // passes of a causal pair
 }
 
+// ---------------------------------------------------------------------------------------
+// Head dimension 256: four waves, one per SIMD, software-pipelined across key blocks like
+// fa_fwd_d256_kernel of the 16-bit path (the paper's Algorithm 2 within one wave):
+//   stage A: S(t+1)^T = K(t+1) Q^T   ||  reference maximum for S(t) (rarely a rescale of O, l),
+//                                        P~(t) = exp2(...), row sums, conversion to e4m3
+//   stage B: O^T += V(t)^T P~(t)^T   ||  mask and row maxima of S(t+1)
+// Score tiles are produced by MfmaFp8VgprAcc into ordinary registers (O lives in the accumulation
+// half of the register file), the K and V blocks travel global -> registers -> LDS one 16-byte
+// chunk at a time spread over the MFMA steps, and the block scales of block t+1 are fetched a
+// block ahead so that no wave waits for a scalar load.  The arithmetic is that of
+// fa_fwd_fp8_kernel, step for step.
+template <bool CAUSAL, bool SCALED>
+__global__ void __launch_bounds__(256, 1)
+fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
+                       const float* __restrict__ q_scale, const float* __restrict__ k_scale,
+                       const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
+                       int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
+    constexpr int D = 256, BC = 64, NW = 4, NT = 256, BR = 128;
+    constexpr int KSTR = D + 16, VSTR = D + 32;  // bytes per LDS row
+    constexpr int KS = D / 64, DT = D / 32;
+    constexpr int CPR = D / 16, CPT = BC * CPR / NT;  // 16-byte chunks per row, per thread and tile
+    constexpr int NA = 2 * KS, NB = DT;               // MFMA steps of stage A (kt, ks) and of stage B (d-tile)
+    constexpr int CH_A = NA / CPT, CH_B = NB / CPT;   // a staging chunk every so many steps
+    static_assert(CPT * CH_A == NA && CPT * CH_B == NB, "chunks must spread evenly over the steps");
+
+    __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][BC * KSTR];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][BC * VSTR];
+    __shared__ __attribute__((aligned(128))) char lds_o[NW * 4096];  // output transposition, 4 KiB per wave
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int col = lane & 31, half = lane >> 5;
+
+    int id = xcd_contiguous(blockIdx.x, total_wg);
+    const int n_items = CAUSAL ? (n_qtiles + 1) / 2 : n_qtiles;
+    const int bh = id / n_items;
+    const int item = id % n_items;
+    const int n_pass = (CAUSAL && n_qtiles - 1 - item != item) ? 2 : 1;
+
+    const size_t head_off = (size_t)bh * N * D;
+    const uint8_t* qh = q + head_off;
+    const int kv_bh = bh / kv_group;  // grouped-query: kv_group query heads per K/V head
+    const __amdgpu_buffer_rsrc_t k_rsrc = make_buffer(k + (size_t)kv_bh * N * D, (uint32_t)N * D);
+    const __amdgpu_buffer_rsrc_t v_rsrc = make_buffer(v + (size_t)kv_bh * N * D, (uint32_t)N * D);
+    const float* ksc = k_scale + (size_t)kv_bh * n_sblocks;
+    const float* vsc = v_scale + (size_t)kv_bh * n_sblocks;
+    const int krow = key_of_row(col);  // key (within a 32-key tile) this lane's A row reads
+    const int tr_row = (lane & 15) >> 1;
+    const int tr_col = 16 * ((lane >> 4) & 1) + 8 * (lane & 1);
+    int unit = 0x7F7F7F7F;  // scale exponents 127 = 1.0 for both MFMA operands
+    asm volatile("" : "+v"(unit));
+
+#pragma nounroll
+    for (int pass = 0; pass < n_pass; ++pass) {
+    const int qt = CAUSAL ? (pass == 0 ? n_qtiles - 1 - item : item) : item;  // the longer tile first
+    const int wave_q0 = qt * BR + wave * 32;
+    const int limit = CAUSAL ? min(wave_q0 + col, N - 1) : N - 1;  // last key this lane's query sees
+
+    float sq = 1.0f;
+    if constexpr (SCALED) sq = q_scale[(size_t)bh * n_sblocks + min(wave_q0 / 128, n_sblocks - 1)];
+    const float sc_q = scale * kLog2e * sq;
+
+    i32x8 qreg[KS];
+    {
+        const int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const uint8_t* p = qh + (size_t)row * D + ks * 64 + half * 32;
+            i32x4 lo = *reinterpret_cast<const i32x4*>(p);
+            i32x4 hi = *reinterpret_cast<const i32x4*>(p + 16);
+            qreg[ks] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+    }
+    f32x16 oacc[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+    // m: running (lazily raised) maximum, in log2 units, of the real scores plus log2 of their V block's scale
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int last_q = min(qt * BR + BR, N) - 1;
+    const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
+
+    float mxp[4];
+    auto need_mask = [&](int t) { return (t * BC + BC > N) || (CAUSAL && t * BC + BC - 1 > wave_q0); };
+    auto mask_block = [&](int t, f32x16 (&s)[2]) {
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                // register r of lane-half `half` is MFMA row 8*(r/4) + 4*half + r%4, which holds key ...
+                const int key = t * BC + kt * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
+                if (key > limit) s[kt][r] = -INFINITY;
+            }
+    };
+    auto max_part = [&](f32x16 (&s)[2], int part) {  // registers 8 part .. 8 part + 7 of the 32
+#pragma unroll
+        for (int i = 8 * part; i < 8 * part + 8; ++i)
+            mxp[i & 3] = i < 4 ? s[0][i] : fmaxf(mxp[i & 3], s[i >> 4][i & 15]);
+    };
+    // step u = (ks, kt) of S^T = K Q^T: the A operand is 32 bytes of a (permuted) K row
+    auto k_read = [&](uint32_t k_rows, int u, i32x4& lo, i32x4& hi) {
+        const uint32_t a = k_rows + ((u % 2) * 32 * KSTR + (u / 2) * 64);
+        lo = lds_load_16B(a);
+        hi = lds_load_16B(a + 16);
+    };
+    auto score_step = [&](f32x16 (&s)[2], uint32_t k_rows, i32x4 (&alo)[2], i32x4 (&ahi)[2], int u) {
+        const int kt = u % 2, ks = u / 2;
+        const i32x8 a = {alo[u % 2][0], alo[u % 2][1], alo[u % 2][2], alo[u % 2][3],
+                         ahi[u % 2][0], ahi[u % 2][1], ahi[u % 2][2], ahi[u % 2][3]};
+        if (u + 2 < NA) k_read(k_rows, u + 2, alo[u % 2], ahi[u % 2]);
+        if (ks == 0) MfmaFp8VgprAcc::first(s[kt], a, qreg[ks], unit);
+        else MfmaFp8VgprAcc::run(s[kt], a, qreg[ks], unit);
+    };
+    auto block_scale = [&](const float* table, int t) {  // scale of the 128-key block that holds key block t
+        return SCALED ? table[min(t * BC / 128, n_sblocks - 1)] : 1.0f;
+    };
+
+    // staging: see fa_fwd_d256_kernel
+    i32x4 kpre[CPT], vpre[CPT];
+    auto load_chunk = [&](__amdgpu_buffer_rsrc_t rsrc, int block_idx, int i) {
+        return buffer_load_16B(rsrc, block_idx * BC * D + (tid + i * NT) * 16);
+    };
+    auto store_chunk = [&](uint8_t* lds, int stride, int i, const i32x4& x) {
+        const int c = tid + i * NT;
+        *reinterpret_cast<i32x4*>(lds + (c / CPR) * stride + (c % CPR) * 16) = x;
+    };
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        kpre[i] = load_chunk(k_rsrc, 0, i);
+        vpre[i] = load_chunk(v_rsrc, 0, i);
+    }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        store_chunk(lds_k[0], KSTR, i, kpre[i]);
+        store_chunk(lds_v[0], VSTR, i, vpre[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < CPT; ++i) {
+        kpre[i] = load_chunk(k_rsrc, 1, i);  // K(1)
+        vpre[i] = load_chunk(v_rsrc, 1, i);  // V(1), written to the LDS during block 0
+    }
+    float sk_cur = block_scale(ksc, 0), sv_cur = block_scale(vsc, 0);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));  // Q loads complete before the loop
+    __syncthreads();
+
+    // ---- prologue: S(0) and its reference maximum (O and l are still zero: nothing to rescale)
+    f32x16 sa[2], sb[2];
+    {
+        uint32_t k_rows = lds_address(lds_k[0]) + krow * KSTR + half * 32;
+        asm volatile("" : "+v"(k_rows));
+        i32x4 alo[2], ahi[2];
+        k_read(k_rows, 0, alo[0], ahi[0]);
+        k_read(k_rows, 1, alo[1], ahi[1]);
+#pragma unroll
+        for (int u = 0; u < NA; ++u) {
+            score_step(sa, k_rows, alo, ahi, u);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) store_chunk(lds_k[1], KSTR, i, kpre[i]);
+        mfma_fp8_result_wait(sa[0], sa[1]);
+        if (need_mask(0)) mask_block(0, sa);
+#pragma unroll
+        for (int part = 0; part < 4; ++part) max_part(sa, part);
+        float lsv = 0.f;
+        if constexpr (SCALED) lsv = __builtin_amdgcn_logf(sv_cur);  // log2
+        m_run = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * (sc_q * sk_cur) + lsv;
+    }
+    __syncthreads();
+
+    // ---- one key block: `cur` holds S(t), `nxt` receives S(t+1)
+    auto block = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+        // the scales of block t+1, for the next call
+        const float sk_next = block_scale(ksc, t + 1), sv_next = block_scale(vsc, t + 1);
+        i32x8 pb;  // P~(t)^T as the B operand: 64 keys
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+        float mb = 0.f, sc_v = 0.f;
+        uint32_t k_rows = lds_address(lds_k[(t + 1) & 1]) + krow * KSTR + half * 32;
+        uint32_t v_tr = lds_address(lds_v[t & 1]) + (8 * half + tr_row) * VSTR + tr_col;
+        asm volatile("" : "+v"(k_rows), "+v"(v_tr));
+
+        // ---- stage A
+        {
+            i32x4 alo[2], ahi[2];
+            k_read(k_rows, 0, alo[0], ahi[0]);
+            k_read(k_rows, 1, alo[1], ahi[1]);
+#pragma unroll
+            for (int u = 0; u < NA; ++u) {
+                score_step(nxt, k_rows, alo, ahi, u);
+                if (u % CH_A == 0) {
+                    store_chunk(lds_v[(t + 1) & 1], VSTR, u / CH_A, vpre[u / CH_A]);
+                    kpre[u / CH_A] = load_chunk(k_rsrc, t + 2, u / CH_A);
+                }
+                if (u == 0) {
+                    // Reference maximum for S(t), in log2 units of the real scores plus log2 of the V block's
+                    // scale (see fa_fwd_fp8_kernel), from the row maxima taken beside the previous block's
+                    // products.  The MFMAs of this stage write the score registers only, so the rare rescale
+                    // of O is in order here.  (Block 0: the prologue has set the reference; no rise.)
+                    float lsv = 0.f;
+                    if constexpr (SCALED) lsv = __builtin_amdgcn_logf(sv_cur);
+                    const float sc = sc_q * sk_cur;
+                    const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * sc + lsv;
+                    const bool raise = mx - m_run > kLazyLog2;
+                    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                        const float f = raise ? fast_exp2(m_run - mx) : 1.0f;
+                        m_run = raise ? mx : m_run;
+                        l_run *= f;
+#pragma unroll
+                        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
+                    }
+                    mb = m_run - kPBias - lsv;
+                    sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
+                    asm volatile("" : "+v"(sc_v));
+                }
+                // four scores of S(t) become one word of P~ per step
+                {
+                    const int kt = u / 4, w = u % 4;
+                    float p[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        p[e] = fast_exp2(__builtin_fmaf(cur[kt][4 * w + e], sc_v, -mb));
+                        ps[e] += p[e];
+                    }
+                    int word = 0;
+                    word = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], word, false);
+                    word = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], word, true);
+                    pb[4 * kt + w] = word;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            float psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            if constexpr (SCALED) psum *= __builtin_amdgcn_rcpf(sv_cur);
+            l_run += psum;
+        }
+
+        // ---- stage B
+        {
+            auto v_read = [&](int dt, i32x2 (&w)[4]) {
+#pragma unroll
+                for (int x = 0; x < 4; ++x) w[x] = lds_read_tr8(v_tr + (16 * x) * VSTR + dt * 32);
+            };
+            i32x2 wbuf[2][4];
+            v_read(0, wbuf[0]);
+            v_read(1, wbuf[1]);
+            const bool mask_next = need_mask(t + 1);
+#pragma unroll
+            for (int u = 0; u < NB; ++u) {
+                const i32x8 a = {wbuf[u % 2][0][0], wbuf[u % 2][0][1], wbuf[u % 2][1][0], wbuf[u % 2][1][1],
+                                 wbuf[u % 2][2][0], wbuf[u % 2][2][1], wbuf[u % 2][3][0], wbuf[u % 2][3][1]};
+                if (u + 2 < NB) v_read(u + 2, wbuf[u % 2]);
+                oacc[u] = mma_fp8(a, pb, oacc[u]);
+                if (u == 0) mfma_fp8_result_wait(nxt[0], nxt[1]);  // written by MFMAs the hazard checker cannot see
+                if (u == 1 && mask_next) mask_block(t + 1, nxt);
+                if (u >= 2 && u < 6) max_part(nxt, u - 2);
+                if (u % CH_B == 0) {
+                    store_chunk(lds_k[t & 1], KSTR, u / CH_B, kpre[u / CH_B]);
+                    vpre[u / CH_B] = load_chunk(v_rsrc, t + 2, u / CH_B);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        sk_cur = sk_next;
+        sv_cur = sv_next;
+        __syncthreads();
+    };
+
+    for (int t = 0; t < n_blocks; t += 2) {
+        block(t, sa, sb);
+        if (t + 1 < n_blocks) block(t + 1, sb, sa);
+    }
+
+    // ---- epilogue: O * s_V / l as bf16 (transposed through a wave-private LDS patch), L
+    {
+        char* patch = lds_o + wave * 4096;
+        const int qi = wave_q0 + col;
+        const float l = sum_both_halves(l_run);
+        store_rows_via_lds<bf16_tag, DT>(oacc, 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2),
+                                         wave_q0, lane);
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l) - kPBias) * kLn2;
+    }
+    }  // passes of a causal pair
+}
+
+static int launch_fp8_d256(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
+                           const float* vs, void* o, float* lse, int B, int H, int H_kv, int N, float scale,
+                           int causal, hipStream_t stream) {
+    constexpr int BR = 128;
+    int n_qtiles = (N + BR - 1) / BR;
+    int n_sblocks = (N + 127) / 128;
+    long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
+    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
+    dim3 grid((unsigned)total), block(256);
+    auto qp = static_cast<const uint8_t*>(q8);
+    auto kp = static_cast<const uint8_t*>(k8);
+    auto vp = static_cast<const uint8_t*>(v8);
+    auto op = static_cast<uint16_t*>(o);
+    const bool scaled = qs != nullptr;
+#define FA_LAUNCH_FP8_D256(C, S)                                                                               \
+    hipLaunchKernelGGL((fa_fwd_fp8_d256_kernel<C, S>), grid, block, 0, stream, qp, kp, vp, qs, ks, vs, op, lse, \
+                       N, n_qtiles, (int)total, n_sblocks, H / H_kv, scale)
+    if (causal) {
+        if (scaled) FA_LAUNCH_FP8_D256(true, true); else FA_LAUNCH_FP8_D256(true, false);
+    } else {
+        if (scaled) FA_LAUNCH_FP8_D256(false, true); else FA_LAUNCH_FP8_D256(false, false);
+    }
+#undef FA_LAUNCH_FP8_D256
+    return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
+}
+
 template <int D, int BC, int NW>
 static int launch_fp8(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
                       const float* vs, void* o, float* lse, int B, int H, int H_kv, int N, float scale, int causal,
@@ -308,7 +622,7 @@ int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* 
         case 128:
             if (small_tile) return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256: return launch_fp8<256, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case 256: return launch_fp8_d256(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }

@@ -14,8 +14,9 @@ instruction that names a register of that range, and any MFMA that takes it as a
 before `need` wait states have passed.  A following MFMA that accumulates into exactly the same
 range is the hardware-interlocked case and is allowed.
 
-The 8-pass 32x32x16 MFMA needs 11 wait states before a VALU read of its result; the compiler
-leaves 12 or more in the code it schedules itself, and `need` defaults to that.
+The 8-pass 32x32x16 MFMA needs 11 wait states before a VALU read of its result and the 16-pass
+32x32x64 e4m3 MFMA 19; the compiler leaves 12 (20) or more in the code it schedules itself, and those
+are the defaults here.
 """
 import re
 import sys
@@ -33,7 +34,7 @@ def _vgprs(text):
     return out
 
 
-def check(asm_text, need=12, horizon=64):
+def check(asm_text, need=12, need_16_pass=20, horizon=64):
     """Returns a list of (function, line number within the function, instruction, wait states so far)."""
     problems = []
     func, in_asm, pending, ln = None, False, [], 0
@@ -62,21 +63,21 @@ def check(asm_text, need=12, horizon=64):
             parts = [a.strip() for a in args.split(",")]
             dst, ab = _vgprs(parts[0]), _vgprs(parts[1]) | _vgprs(parts[2])
             src_c = _vgprs(parts[3]) if len(parts) > 3 else set()
-            for regs, waited in pending:
-                if regs & ab and waited < need:
+            for regs, waited, req in pending:
+                if regs & ab and waited < req:
                     problems.append((func, ln, text, waited))
-                if regs & src_c and regs != src_c and waited < need:
+                if regs & src_c and regs != src_c and waited < req:
                     problems.append((func, ln, text, waited))
-            pending = [[regs, waited + states] for regs, waited in pending]
+            pending = [[regs, waited + states, req] for regs, waited, req in pending]
             if in_asm and dst:
                 pending = [p for p in pending if p[0] != dst]
-                pending.append([dst, 0])
+                pending.append([dst, 0, need_16_pass if "f8f6f4" in op else need])
         else:
             touched = _vgprs(args)
-            for regs, waited in pending:
-                if regs & touched and waited < need:
+            for regs, waited, req in pending:
+                if regs & touched and waited < req:
                     problems.append((func, ln, text, waited))
-            pending = [[regs, waited + states] for regs, waited in pending]
+            pending = [[regs, waited + states, req] for regs, waited, req in pending]
         pending = [p for p in pending if p[1] < horizon]
     return problems
 
