@@ -532,8 +532,22 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 }
 
             // ---- P = exp(S - L), dS = P o (dP - D), packed as the B operand of the dQ product
+            // keys past N, and keys after the query when causal, get S = -inf (P = 0): one uniform branch per
+            // block, not a select per element in every block
+            // (At d = 256, one wave per SIMD, the score tiles sit in the accumulation half of the register
+            // file and a masked write-back there costs more than it saves: that instantiation selects per element.)
+            constexpr bool MASK_BRANCH = NW == 8;
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
             const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+            if (MASK_BRANCH && need_mask) {
+#pragma unroll
+                for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                        if (key > limit) sacc[kt][r] = -INFINITY;
+                    }
+            }
             i32x4 dsb[SL];
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt) {
@@ -541,8 +555,8 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     float p = fast_exp2(__builtin_fmaf(sacc[kt][r], sc, -l2));
-                    if (need_mask) {
-                        int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (!MASK_BRANCH && need_mask) {
+                        const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                         p = key > limit ? 0.f : p;
                     }
                     ds[r] = p * (pacc[kt][r] - dq_row);
