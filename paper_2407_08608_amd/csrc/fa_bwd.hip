@@ -502,8 +502,21 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     };
     load_tile(0);
     store_tile(0);
+    // One wave per SIMD (d = 256): the kernel may use more than 256 registers per lane, MFMA results
+    // then land in the accumulation half of the register file, and the score tiles would pay a copy per
+    // element on their way to the exponentials.  They are produced by MfmaVgprAcc into ordinary
+    // registers instead (Q_i, dO_i, touched by MFMA alone, go to the accumulation half), and the next
+    // block's K and V travel in 16-byte chunks spread over the MFMA steps: as one burst, the 16 loads
+    // of a wave keep it in its own issue for over a thousand cycles (see fa_fwd_d256_kernel).
+    constexpr bool ONE_WAVE = NW == 4;
+    constexpr int NSTEP = KS * KT;  // MFMA steps of either GEMM group; a staging chunk every CH_EVERY of them
+    constexpr int CH_EVERY = ONE_WAVE ? NSTEP / CPT : 1;
+    static_assert(!ONE_WAVE || (CPT * CH_EVERY == NSTEP && SL * DT == NSTEP), "chunks must spread evenly");
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]), "+v"(doreg[ks]));  // loads done before the loop
+    for (int ks = 0; ks < KS; ++ks) {  // loads done before the loop
+        if constexpr (ONE_WAVE) asm volatile("" : "+a"(qreg[ks]), "+a"(doreg[ks]));
+        else asm volatile("" : "+v"(qreg[ks]), "+v"(doreg[ks]));
+    }
     __syncthreads();
 
     const int tr_row = (lane & 15) >> 2;
@@ -513,9 +526,12 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
         const int st = t & 1;
         const int key0 = t * BC;
         const bool more = (t + 1 < n_blocks);
-        if (more) load_tile(key0 + BC);
+        // a wave whose queries all precede this block has nothing to add (causal).  With one wave per SIMD every
+        // wave works every block (a fully masked one adds zeros): the branch around the interleaved staging
+        // costs that instantiation a hundred registers.
+        const bool wave_active = !CAUSAL || ONE_WAVE || key0 <= wave_q0 + 31;
+        if (more && !(ONE_WAVE && wave_active)) load_tile(key0 + BC);
 
-        const bool wave_active = !CAUSAL || key0 <= wave_q0 + 31;
         if (wave_active) {
             // ---- S^T = K_j Q_i^T and dP^T = V_j dO_i^T
             f32x16 sacc[KT], pacc[KT];
@@ -527,26 +543,48 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                 for (int kt = 0; kt < KT; ++kt) {
                     i32x4 ak = *reinterpret_cast<const i32x4*>(lds_k[st] + kbase + kt * 32 * RSTR + ks * 16);
                     i32x4 av = *reinterpret_cast<const i32x4*>(lds_v[st] + vbase + kt * 32 * VSTR + ks * 16);
-                    sacc[kt] = E::mma(ak, qreg[ks], ks == 0 ? zero : sacc[kt]);
-                    pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? zero : pacc[kt]);
+                    if constexpr (ONE_WAVE) {
+                        if (ks == 0) {
+                            MfmaVgprAcc<Tag>::first(sacc[kt], ak, qreg[ks]);
+                            MfmaVgprAcc<Tag>::first(pacc[kt], av, doreg[ks]);
+                        } else {
+                            MfmaVgprAcc<Tag>::run(sacc[kt], ak, qreg[ks]);
+                            MfmaVgprAcc<Tag>::run(pacc[kt], av, doreg[ks]);
+                        }
+                        const int u = ks * KT + kt;
+                        if (more && u % CH_EVERY == 0) {
+                            const int i = u / CH_EVERY;
+                            kpre[i] = buffer_load_16B(k_rsrc, (key0 + BC) * D * 2 + (tid + i * NT) * 16);
+                            vpre[i] = buffer_load_16B(v_rsrc, (key0 + BC) * D * 2 + (tid + i * NT) * 16);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else {
+                        sacc[kt] = E::mma(ak, qreg[ks], ks == 0 ? zero : sacc[kt]);
+                        pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? zero : pacc[kt]);
+                    }
                 }
+            if constexpr (ONE_WAVE) {  // results of MFMAs the hazard checker cannot see
+                static_assert(!ONE_WAVE || KT == 2, "two score tiles per GEMM");
+                mfma_result_wait(sacc[0], sacc[1]);
+                mfma_result_wait(pacc[0], pacc[1]);
+            }
 
             // ---- P = exp(S - L), dS = P o (dP - D), packed as the B operand of the dQ product
             // keys past N, and keys after the query when causal, get S = -inf (P = 0): one uniform branch per
             // block, not a select per element in every block
-            // (At d = 256, one wave per SIMD, the score tiles sit in the accumulation half of the register
-            // file and a masked write-back there costs more than it saves: that instantiation selects per element.)
-            constexpr bool MASK_BRANCH = NW == 8;
+            constexpr bool MASK_BRANCH = true;
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
             const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
             if (MASK_BRANCH && need_mask) {
+                // compile-time key offsets against one per-lane bound (kept opaque: the compiler otherwise
+                // hoists 32 per-element key indices out of the block loop into registers of their own)
+                int bound = limit - key0 - 4 * half;
+                asm volatile("" : "+v"(bound));
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                        if (key > limit) sacc[kt][r] = -INFINITY;
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) sacc[kt][r] = -INFINITY;
             }
             i32x4 dsb[SL];
 #pragma unroll
@@ -581,10 +619,19 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     i32x2 hi = lds_read_tr16(p0 + 8 * RSTR);
                     i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
                     acc[dt] = E::mma(a, dsb[sl], acc[dt]);
+                    if constexpr (ONE_WAVE) {
+                        const int u = sl * DT + dt;
+                        if (more && u % CH_EVERY == 0) {  // the chunks loaded beside the first GEMM group go to the other buffers
+                            const int c = tid + (u / CH_EVERY) * NT;
+                            *reinterpret_cast<i32x4*>(lds_k[st ^ 1] + (c / CPR) * RSTR + (c % CPR) * 8) = kpre[u / CH_EVERY];
+                            *reinterpret_cast<i32x4*>(lds_v[st ^ 1] + (c / CPR) * VSTR + (c % CPR) * 8) = vpre[u / CH_EVERY];
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
         }
 
-        if (more) store_tile(st ^ 1);
+        if (more && !(ONE_WAVE && wave_active)) store_tile(st ^ 1);
         __syncthreads();
     }
 
