@@ -394,13 +394,15 @@ fa_fwd_d256_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
     float mxp[4];
     auto need_mask = [&](int t) { return (t * BC + BC > N) || (CAUSAL && t * BC + BC - 1 > wave_q0); };
     auto mask_block = [&](int t, f32x16 (&s)[2]) {  // keys past N, and keys after the query when causal
+        // compile-time key offsets against one per-lane bound (kept opaque: the compiler otherwise gives the
+        // 32 per-element key indices registers of their own)
+        int bound = limit - t * BC - 4 * half;
+        asm volatile("" : "+v"(bound));
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = t * BC + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                if (key > limit) s[kt][r] = -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r)
+                if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) s[kt][r] = -INFINITY;
     };
     auto max_part = [&](f32x16 (&s)[2], int part) {  // registers 8 part .. 8 part + 7 of the 32
 #pragma unroll

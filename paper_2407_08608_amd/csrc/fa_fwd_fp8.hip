@@ -357,14 +357,15 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
     float mxp[4];
     auto need_mask = [&](int t) { return (t * BC + BC > N) || (CAUSAL && t * BC + BC - 1 > wave_q0); };
     auto mask_block = [&](int t, f32x16 (&s)[2]) {
+        // register r of lane-half `half` holds key 16 (r / 8) + 8 half + r % 8 of its 32-key tile (the rows of
+        // the K operand are permuted, see key_of_row); compile-time offsets against one opaque per-lane bound
+        int bound = limit - t * BC - 8 * half;
+        asm volatile("" : "+v"(bound));
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                // register r of lane-half `half` is MFMA row 8*(r/4) + 4*half + r%4, which holds key ...
-                const int key = t * BC + kt * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
-                if (key > limit) s[kt][r] = -INFINITY;
-            }
+            for (int r = 0; r < 16; ++r)
+                if (kt * 32 + 16 * (r >> 3) + (r & 7) > bound) s[kt][r] = -INFINITY;
     };
     auto max_part = [&](f32x16 (&s)[2], int part) {  // registers 8 part .. 8 part + 7 of the 32
 #pragma unroll
