@@ -153,6 +153,23 @@ def test_fp8_forward_v_scales_jump_up_and_down_by_large_factors(causal):
     assert (err <= 2.0 ** -4 * 1.05 * p_abs + 2.0 ** -8 * np.abs(o_ref) + 1e-6).all()
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("d", [64, 128, 256])
+def test_fp8_unit_scale_entry_point_matches_oracle(d, causal):
+    """fa_fwd with dtype e4m3 takes the codes at unit scale: every head dimension has an instantiation
+    without block scales of its own."""
+    B, H, N = 1, 2, 333
+    rng = np.random.default_rng(43 + d)
+    qc, kc, vc = (f8.e4m3_encode(rng.standard_normal((B, H, N, d))) for _ in range(3))
+    dev = [torch.from_numpy(c).cuda() for c in (qc, kc, vc)]
+    o, lse = binding.fa_fwd(*dev, d ** -0.5, causal, dtype=binding.FA_FP8_E4M3)
+    torch.cuda.synchronize()
+    vd = f8.e4m3_decode(vc)
+    o_ref, l_ref = oracle.attention_fwd(f8.e4m3_decode(qc), f8.e4m3_decode(kc), vd, d ** -0.5, causal)
+    assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(vd).max() * 1.05 + 2.0 ** -7
+    assert max_abs(f64(lse), l_ref) <= 2e-3
+
+
 def test_fp8_unit_scale_entry_point_and_constant_values():
     B, H, N, d = 1, 2, 200, 128
     rng = np.random.default_rng(41)

@@ -68,7 +68,7 @@ def test_gqa_equals_ordinary_entry_point_on_repeated_heads_bitwise():
 
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("H,H_kv", [(4, 2), (4, 1)])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [64, 128, 256])
 def test_gqa_forward_fp8_block_scaled(d, H, H_kv, causal):
     B, N = 2, 300
     q, k, v = _tensors(120 + d + H_kv, B, H, H_kv, N, d, "bf16")
