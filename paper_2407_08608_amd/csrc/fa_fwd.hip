@@ -193,13 +193,15 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                 for (int rq = 0; rq < RQ; ++rq) {
                     int qi = wave_q0 + rq * 32 + col;
                     int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+                    // compile-time key offsets against one opaque per-lane bound: a compare and a select per
+                    // score, no index arithmetic
+                    int bound = limit - key0 - 4 * half;
+                    asm volatile("" : "+v"(bound));
 #pragma unroll
                     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                            if (key > limit) sacc[rq][kt][r] = -INFINITY;
-                        }
+                        for (int r = 0; r < 16; ++r)
+                            if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) sacc[rq][kt][r] = -INFINITY;
                 }
             }
 

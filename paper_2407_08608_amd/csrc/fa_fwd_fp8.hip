@@ -174,14 +174,15 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
             if (need_mask) {
                 int qi = wave_q0 + col;
                 int limit = CAUSAL ? min(qi, N - 1) : N - 1;
+                // register r of lane-half `half` holds key 16 (r / 8) + 8 half + r % 8 of its 32-key tile (the
+                // rows of the K operand are permuted); compile-time offsets against one opaque per-lane bound
+                int bound = limit - key0 - 8 * half;
+                asm volatile("" : "+v"(bound));
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        // register r of lane-half `half` is MFMA row 8*(r/4) + 4*half + r%4
-                        int key = key0 + kt * 32 + 16 * (r >> 3) + 8 * half + (r & 7);
-                        if (key > limit) sacc[kt][r] = -INFINITY;
-                    }
+                    for (int r = 0; r < 16; ++r)
+                        if (kt * 32 + 16 * (r >> 3) + (r & 7) > bound) sacc[kt][r] = -INFINITY;
             }
 
             // ---- online softmax in log2 units of the real scores.  Independent chains for the maximum
