@@ -102,11 +102,11 @@ static __device__ __forceinline__ void mfma_result_wait(f32x16& x) { asm volatil
 struct MfmaFp8VgprAcc {
     static __device__ __forceinline__ void run(f32x16& acc, const i32x8& a, const i32x8& b, int unit) {
         asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0]"
-                     : "+v"(acc) : "v"(a), "v"(b), "v"(unit));
+                     : "+v"(acc) : "v"(a), "a"(b), "v"(unit));
     }
     static __device__ __forceinline__ void first(f32x16& acc, const i32x8& a, const i32x8& b, int unit) {
         asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, 0, %3, %3 op_sel_hi:[0,0,0]"
-                     : "=&v"(acc) : "v"(a), "v"(b), "v"(unit));
+                     : "=&v"(acc) : "v"(a), "a"(b), "v"(unit));
     }
 };
 static __device__ __forceinline__ void mfma_fp8_result_wait(f32x16& x, f32x16& y) {

@@ -417,7 +417,7 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
     }
     float sk_cur = block_scale(ksc, 0), sv_cur = block_scale(vsc, 0);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));  // Q loads complete before the loop
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qreg[ks]));  // Q loads complete; Q moves to the accumulation half
     __syncthreads();
 
     // ---- prologue: S(0) and its reference maximum (O and l are still zero: nothing to rescale)
