@@ -113,6 +113,15 @@ static __device__ __forceinline__ void mfma_fp8_result_wait(f32x16& x, f32x16& y
     asm volatile("s_nop 15\n\ts_nop 4" : "+v"(x), "+v"(y));
 }
 
+// Workgroup barrier for LDS traffic only: waits for this wave's LDS accesses, not for its global loads
+// (__syncthreads() waits for both, which would expose the latency of staging loads that are meant to
+// stay in flight across the barrier; their destination registers are waited for where they are used).
+static __device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // 32-bit LDS byte address of a __shared__ object, and loads through such an address: a base kept
 // in one register with compile-time offsets lets every read use the instruction's immediate
 // offset field instead of an address computation of its own.

@@ -387,11 +387,21 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         if (ks == 0) MfmaFp8VgprAcc::first(s[kt], a, qreg[ks], unit);
         else MfmaFp8VgprAcc::run(s[kt], a, qreg[ks], unit);
     };
-    auto block_scale = [&](const float* table, int t) {  // scale of the 128-key block that holds key block t
-        return SCALED ? table[min(t * BC / 128, n_sblocks - 1)] : 1.0f;
+    // Scale of the 128-key block that holds key block t.  Fetched with a vector load (the index is made
+    // opaque so that the compiler cannot turn it into a scalar load): scalar loads share their counter
+    // with the LDS reads, and the first LDS wait after one would make the wave sit out its latency.
+    auto block_scale = [&](const float* table, int t) {
+        if constexpr (!SCALED) return 1.0f;
+        int idx = min(t * BC / 128, n_sblocks - 1);
+        asm volatile("" : "+v"(idx));
+        return table[idx];
     };
 
-    // staging: see fa_fwd_d256_kernel
+    // Staging as in fa_fwd_d256_kernel, one 16-byte chunk per thread at a time spread over the MFMA
+    // steps, but with a whole block of lead: the stages of this kernel are shorter than a global load,
+    //   stage A of block t: write the K(t+2) chunk loaded in block t-1, load the K(t+3) chunk
+    //   stage B of block t: write the V(t+1) chunk loaded in block t-1, load the V(t+2) chunk
+    // (K(t+2) replaces K(t), last read in block t-1; V(t+1) replaces V(t-1), last read in block t-1.)
     i32x4 kpre[CPT], vpre[CPT];
     auto load_chunk = [&](__amdgpu_buffer_rsrc_t rsrc, int block_idx, int i) {
         return buffer_load_16B(rsrc, block_idx * BC * D + (tid + i * NT) * 16);
@@ -411,10 +421,7 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         store_chunk(lds_v[0], VSTR, i, vpre[i]);
     }
 #pragma unroll
-    for (int i = 0; i < CPT; ++i) {
-        kpre[i] = load_chunk(k_rsrc, 1, i);  // K(1)
-        vpre[i] = load_chunk(v_rsrc, 1, i);  // V(1), written to the LDS during block 0
-    }
+    for (int i = 0; i < CPT; ++i) kpre[i] = load_chunk(k_rsrc, 1, i);  // K(1)
     float sk_cur = block_scale(ksc, 0), sv_cur = block_scale(vsc, 0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qreg[ks]));  // Q loads complete; Q moves to the accumulation half
@@ -435,6 +442,14 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         }
 #pragma unroll
         for (int i = 0; i < CPT; ++i) store_chunk(lds_k[1], KSTR, i, kpre[i]);
+        // The loads in flight at the loop's entry are issued in the order the loop itself issues them (K
+        // chunks, then V chunks): the wait counts inside the loop are compile-time numbers that must hold
+        // on both paths into it, and an entry with fewer loads behind a chunk than the steady state has
+        // would make every iteration wait for its newest loads.
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) kpre[i] = load_chunk(k_rsrc, 2, i);  // K(2), written to the LDS during block 0
+#pragma unroll
+        for (int i = 0; i < CPT; ++i) vpre[i] = load_chunk(v_rsrc, 1, i);  // V(1), likewise
         mfma_fp8_result_wait(sa[0], sa[1]);
         if (need_mask(0)) mask_block(0, sa);
 #pragma unroll
@@ -465,8 +480,8 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
             for (int u = 0; u < NA; ++u) {
                 score_step(nxt, k_rows, alo, ahi, u);
                 if (u % CH_A == 0) {
-                    store_chunk(lds_v[(t + 1) & 1], VSTR, u / CH_A, vpre[u / CH_A]);
-                    kpre[u / CH_A] = load_chunk(k_rsrc, t + 2, u / CH_A);
+                    store_chunk(lds_k[t & 1], KSTR, u / CH_A, kpre[u / CH_A]);
+                    kpre[u / CH_A] = load_chunk(k_rsrc, t + 3, u / CH_A);
                 }
                 if (u == 0) {
                     // Reference maximum for S(t), in log2 units of the real scores plus log2 of the V block's
@@ -503,6 +518,9 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
                     int word = 0;
                     word = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], word, false);
                     word = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], word, true);
+                    // the word must exist here: left free, the compiler sinks the exponentials (and with them
+                    // the products of stage B) past the branches and the barrier below, out of this stream
+                    asm volatile("" : "+v"(word), "+v"(ps[0]), "+v"(ps[1]), "+v"(ps[2]), "+v"(ps[3]));
                     pb[4 * kt + w] = word;
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -528,11 +546,12 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
                                  wbuf[u % 2][2][0], wbuf[u % 2][2][1], wbuf[u % 2][3][0], wbuf[u % 2][3][1]};
                 if (u + 2 < NB) v_read(u + 2, wbuf[u % 2]);
                 oacc[u] = mma_fp8(a, pb, oacc[u]);
+                asm volatile("" : "+a"(oacc[u]));  // issued here, not sunk past the barrier
                 if (u == 0) mfma_fp8_result_wait(nxt[0], nxt[1]);  // written by MFMAs the hazard checker cannot see
                 if (u == 1 && mask_next) mask_block(t + 1, nxt);
                 if (u >= 2 && u < 6) max_part(nxt, u - 2);
                 if (u % CH_B == 0) {
-                    store_chunk(lds_k[t & 1], KSTR, u / CH_B, kpre[u / CH_B]);
+                    store_chunk(lds_v[(t + 1) & 1], VSTR, u / CH_B, vpre[u / CH_B]);
                     vpre[u / CH_B] = load_chunk(v_rsrc, t + 2, u / CH_B);
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -540,7 +559,7 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         }
         sk_cur = sk_next;
         sv_cur = sv_next;
-        __syncthreads();
+        lds_barrier();  // the chunk loads of this block stay in flight
     };
 
     for (int t = 0; t < n_blocks; t += 2) {
