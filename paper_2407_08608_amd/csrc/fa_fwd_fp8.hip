@@ -282,19 +282,25 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 // chunk at a time spread over the MFMA steps, and the block scales of block t+1 are fetched a
 // block ahead so that no wave waits for a scalar load.  The arithmetic is that of
 // fa_fwd_fp8_kernel, step for step.
-template <bool CAUSAL, bool SCALED>
-__global__ void __launch_bounds__(256, 1)
-fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
+template <int D, int NW, bool CAUSAL, bool SCALED>
+__global__ void __launch_bounds__(NW * 64, NW == 4 ? 1 : 2)
+fa_fwd_fp8_pipe_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, const uint8_t* __restrict__ v,
                        const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                        const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
                        int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
-    constexpr int D = 256, BC = 64, NW = 4, NT = 256, BR = 128;
+    constexpr int BC = 64, NT = NW * 64, BR = NW * 32;
+    // One wave per SIMD (d = 256, four waves): score MFMAs in inline assembly with explicit waits.  Two waves
+    // per SIMD (d = 128, eight waves): at most 256 registers per lane, every MFMA result is in ordinary
+    // registers anyway and the compiler's own MFMAs and hazard handling do.
+    constexpr bool ONE_WAVE = NW == 4;
     constexpr int KSTR = D + 16, VSTR = D + 32;  // bytes per LDS row
     constexpr int KS = D / 64, DT = D / 32;
     constexpr int CPR = D / 16, CPT = BC * CPR / NT;  // 16-byte chunks per row, per thread and tile
     constexpr int NA = 2 * KS, NB = DT;               // MFMA steps of stage A (kt, ks) and of stage B (d-tile)
     constexpr int CH_A = NA / CPT, CH_B = NB / CPT;   // a staging chunk every so many steps
     static_assert(CPT * CH_A == NA && CPT * CH_B == NB, "chunks must spread evenly over the steps");
+    static_assert(NA == 4 || NA == 8, "eight words of P~ over the steps of stage A");
+    constexpr int WPS = 8 / NA;  // words of P~ (four scores each) per step of stage A
 
     __shared__ __attribute__((aligned(16))) uint8_t lds_k[2][BC * KSTR];
     __shared__ __attribute__((aligned(16))) uint8_t lds_v[2][BC * VSTR];
@@ -384,8 +390,13 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         const i32x8 a = {alo[u % 2][0], alo[u % 2][1], alo[u % 2][2], alo[u % 2][3],
                          ahi[u % 2][0], ahi[u % 2][1], ahi[u % 2][2], ahi[u % 2][3]};
         if (u + 2 < NA) k_read(k_rows, u + 2, alo[u % 2], ahi[u % 2]);
-        if (ks == 0) MfmaFp8VgprAcc::first(s[kt], a, qreg[ks], unit);
-        else MfmaFp8VgprAcc::run(s[kt], a, qreg[ks], unit);
+        if constexpr (ONE_WAVE) {
+            if (ks == 0) MfmaFp8VgprAcc::first(s[kt], a, qreg[ks], unit);
+            else MfmaFp8VgprAcc::run(s[kt], a, qreg[ks], unit);
+        } else {
+            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            s[kt] = mma_fp8(a, qreg[ks], ks == 0 ? zero : s[kt]);
+        }
     };
     // Scale of the 128-key block that holds key block t.  Fetched with a vector load (the index is made
     // opaque so that the compiler cannot turn it into a scalar load): scalar loads share their counter
@@ -424,7 +435,10 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
     for (int i = 0; i < CPT; ++i) kpre[i] = load_chunk(k_rsrc, 1, i);  // K(1)
     float sk_cur = block_scale(ksc, 0), sv_cur = block_scale(vsc, 0);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+a"(qreg[ks]));  // Q loads complete; Q moves to the accumulation half
+    for (int ks = 0; ks < KS; ++ks) {  // Q loads complete; with one wave per SIMD, Q moves to the accumulation half
+        if constexpr (ONE_WAVE) asm volatile("" : "+a"(qreg[ks]));
+        else asm volatile("" : "+v"(qreg[ks]));
+    }
     __syncthreads();
 
     // ---- prologue: S(0) and its reference maximum (O and l are still zero: nothing to rescale)
@@ -450,7 +464,7 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
         for (int i = 0; i < CPT; ++i) kpre[i] = load_chunk(k_rsrc, 2, i);  // K(2), written to the LDS during block 0
 #pragma unroll
         for (int i = 0; i < CPT; ++i) vpre[i] = load_chunk(v_rsrc, 1, i);  // V(1), likewise
-        mfma_fp8_result_wait(sa[0], sa[1]);
+        if constexpr (ONE_WAVE) mfma_fp8_result_wait(sa[0], sa[1]);
         if (need_mask(0)) mask_block(0, sa);
 #pragma unroll
         for (int part = 0; part < 4; ++part) max_part(sa, part);
@@ -506,9 +520,10 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
                     sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
                     asm volatile("" : "+v"(sc_v));
                 }
-                // four scores of S(t) become one word of P~ per step
-                {
-                    const int kt = u / 4, w = u % 4;
+                // four scores of S(t) become one word of P~, WPS words per step
+#pragma unroll
+                for (int w2 = 0; w2 < WPS; ++w2) {
+                    const int kt = (u * WPS + w2) / 4, w = (u * WPS + w2) % 4;
                     float p[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -546,10 +561,21 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
                                  wbuf[u % 2][2][0], wbuf[u % 2][2][1], wbuf[u % 2][3][0], wbuf[u % 2][3][1]};
                 if (u + 2 < NB) v_read(u + 2, wbuf[u % 2]);
                 oacc[u] = mma_fp8(a, pb, oacc[u]);
-                asm volatile("" : "+a"(oacc[u]));  // issued here, not sunk past the barrier
-                if (u == 0) mfma_fp8_result_wait(nxt[0], nxt[1]);  // written by MFMAs the hazard checker cannot see
+                // issued here, not sunk past the barrier
+                if constexpr (ONE_WAVE) asm volatile("" : "+a"(oacc[u]));
+                else asm volatile("" : "+v"(oacc[u]));
+                if constexpr (ONE_WAVE) {
+                    if (u == 0) mfma_fp8_result_wait(nxt[0], nxt[1]);  // written by MFMAs the hazard checker cannot see
+                }
                 if (u == 1 && mask_next) mask_block(t + 1, nxt);
-                if (u >= 2 && u < 6) max_part(nxt, u - 2);
+                if constexpr (NB == 8) {
+                    if (u >= 2 && u < 6) max_part(nxt, u - 2);
+                } else {
+                    if (u >= 2) {
+                        max_part(nxt, 2 * (u - 2));
+                        max_part(nxt, 2 * (u - 2) + 1);
+                    }
+                }
                 if (u % CH_B == 0) {
                     store_chunk(lds_v[(t + 1) & 1], VSTR, u / CH_B, vpre[u / CH_B]);
                     vpre[u / CH_B] = load_chunk(v_rsrc, t + 2, u / CH_B);
@@ -579,22 +605,23 @@ fa_fwd_fp8_d256_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
     }  // passes of a causal pair
 }
 
-static int launch_fp8_d256(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
+template <int D, int NW>
+static int launch_fp8_pipe(const void* q8, const void* k8, const void* v8, const float* qs, const float* ks,
                            const float* vs, void* o, float* lse, int B, int H, int H_kv, int N, float scale,
                            int causal, hipStream_t stream) {
-    constexpr int BR = 128;
+    constexpr int BR = NW * 32;
     int n_qtiles = (N + BR - 1) / BR;
     int n_sblocks = (N + 127) / 128;
     long total = (long)B * H * (causal ? (n_qtiles + 1) / 2 : n_qtiles);  // causal: tiles are paired up
     if (total > 0x7fffffffL) return FA_ERR_SHAPE;
-    dim3 grid((unsigned)total), block(256);
+    dim3 grid((unsigned)total), block(NW * 64);
     auto qp = static_cast<const uint8_t*>(q8);
     auto kp = static_cast<const uint8_t*>(k8);
     auto vp = static_cast<const uint8_t*>(v8);
     auto op = static_cast<uint16_t*>(o);
     const bool scaled = qs != nullptr;
 #define FA_LAUNCH_FP8_D256(C, S)                                                                               \
-    hipLaunchKernelGGL((fa_fwd_fp8_d256_kernel<C, S>), grid, block, 0, stream, qp, kp, vp, qs, ks, vs, op, lse, \
+    hipLaunchKernelGGL((fa_fwd_fp8_pipe_kernel<D, NW, C, S>), grid, block, 0, stream, qp, kp, vp, qs, ks, vs, op, lse, \
                        N, n_qtiles, (int)total, n_sblocks, H / H_kv, scale)
     if (causal) {
         if (scaled) FA_LAUNCH_FP8_D256(true, true); else FA_LAUNCH_FP8_D256(true, false);
@@ -642,8 +669,9 @@ int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* 
             return launch_fp8<64, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 128:
             if (small_tile) return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+            // (fa_fwd_fp8_pipe_kernel<128, 8>, two waves per SIMD, is correct and measured 5 % slower than this)
             return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256: return launch_fp8_d256(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case 256: return launch_fp8_pipe<256, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
 }
