@@ -471,6 +471,10 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     }
     const float l2 = lse[(size_t)bh * N + qrow] * kLog2e;
     const float dq_row = dvec[(size_t)bh * N + qrow];
+    constexpr bool NEG_D_START = D == 64;
+    f32x16 negd;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) negd[r] = -dq_row;
 
     f32x16 acc[DT];
 #pragma unroll
@@ -560,7 +564,9 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                         __builtin_amdgcn_sched_barrier(0);
                     } else {
                         sacc[kt] = E::mma(ak, qreg[ks], ks == 0 ? zero : sacc[kt]);
-                        pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? zero : pacc[kt]);
+                        // where registers allow, dP starts from -D (a lane owns one query, so D is one value per
+                        // lane, kept as a 16-register constant): dP - D comes out of the MFMAs
+                        pacc[kt] = E::mma(av, doreg[ks], ks == 0 ? (NEG_D_START ? negd : zero) : pacc[kt]);
                     }
                 }
             if constexpr (ONE_WAVE) {  // results of MFMAs the hazard checker cannot see
@@ -597,7 +603,7 @@ fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                         const int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
                         p = key > limit ? 0.f : p;
                     }
-                    ds[r] = p * (pacc[kt][r] - dq_row);
+                    ds[r] = NEG_D_START ? p * pacc[kt][r] : p * (pacc[kt][r] - dq_row);
                 }
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
