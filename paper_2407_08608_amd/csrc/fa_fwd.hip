@@ -1048,11 +1048,13 @@ static int launch_d256(const void* q, const void* k, const void* v, void* o, flo
 }
 
 // Kernel choice (measured on MI355X at the 16k-token benchmark shapes):
-//   d = 128: the eight-wave ping-pong kernel above 512 keys (causal tiles are paired into items
-//     of equal length there, so its coarser tiles cost no balance); shorter problems keep 128-row
-//     workgroups of four waves, which fill the chip better.
+//   d = 128: the eight-wave ping-pong kernel for long sequences (causal tiles are paired into
+//     items of equal length there, so its coarser tiles cost no balance); shorter problems keep
+//     128-row workgroups of four waves, which fill the chip better and waste less of a tile on
+//     the diagonal.  The two cross between 640 and 768 keys without a mask and near 1400 with one
+//     (measured at 16k and 64k tokens per launch).
 //   d = 64: eight waves share each K/V block (256 query rows per workgroup, two waves per SIMD),
-//     four waves for short problems.
+//     four waves for short problems (crossover near 700 keys without a mask, 1300 with one).
 //   d = 256: the 128-register output accumulator allows only one wave per SIMD; fa_fwd_d256_kernel
 //     pipelines the softmax of one block under the score MFMAs of the next inside that wave.
 template <typename Tag>
@@ -1070,13 +1072,13 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
             default: return FA_ERR_SHAPE;
         }
     }
-    const bool small_tile = N <= 512;
     switch (d) {
         case 64:
-            if (small_tile) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            if (N <= (causal ? 1280 : 640)) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 128:
-            if (N <= 512) return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            if (N <= (causal ? 1408 : 640))
+                return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
             return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         case 256: return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;

@@ -96,8 +96,9 @@ def _fwd_fp8_gpu(codes, scales, scale, causal):
 
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("d", [64, 128, 256])
-@pytest.mark.parametrize("N", [1, 100, 256, 700])
+@pytest.mark.parametrize("N", [1, 100, 256, 700, 1500])
 def test_fp8_forward_matches_model_oracle(N, d, causal):
+    # 1500 keys: past the length up to which d = 128 keeps its four-wave tile, with a ragged tail
     B, H = 2, 2
     _, codes, scales = _prepare(30 + N + d, B, H, N, d, heavy=False)
     scale = d ** -0.5
@@ -109,6 +110,19 @@ def test_fp8_forward_matches_model_oracle(N, d, causal):
     assert max_abs(f64(o), o_ref) <= bound
     if N >= 256:
         assert rmse(f64(o), o_ref) <= 1.5e-2
+    assert max_abs(f64(lse), l_ref) <= 2e-3
+
+
+def test_fp8_forward_d64_eight_wave_tile_ragged():
+    # d = 64 without a mask switches to its 256-query tile only above 3072 keys
+    B, H, N, d = 1, 2, 3300, 64
+    _, codes, scales = _prepare(39, B, H, N, d, heavy=False)
+    o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, False)
+    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
+    o_ref, l_ref = oracle.attention_fwd(*deq, d ** -0.5, False)
+    assert np.isfinite(f64(o)).all()
+    assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
+    assert rmse(f64(o), o_ref) <= 1.5e-2
     assert max_abs(f64(lse), l_ref) <= 2e-3
 
 

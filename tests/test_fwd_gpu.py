@@ -55,9 +55,10 @@ def test_fp32_ragged(N, causal):
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("d", [64, 128, 256])
-@pytest.mark.parametrize("N", [1, 7, 64, 129, 257, 1000])
+@pytest.mark.parametrize("N", [1, 7, 64, 129, 257, 1000, 1500])
 def test_16bit_small_and_ragged(N, d, causal, dtype):
-    # N = 64..1000 spans 1..16 key blocks with ragged tails; several query tiles per head
+    # N = 64..1500 spans 1..24 key blocks with ragged tails; several query tiles per head; 1000 and
+    # 1500 keys sit on either side of the lengths where the 256-query tiles take over
     q, k, v = inputs.qkv(3 + N, 2, 3, N, d, dtype)
     _check_full(q, k, v, d ** -0.5, causal)
 
@@ -75,7 +76,7 @@ def test_bf16_every_block_visited_once(N, causal):
 @pytest.mark.parametrize("N,causal", [(1024, False), (1031, False), (1100, False), (1345, False), (2049, False),
                                       (4096, True), (4129, True), (4200, True)])
 def test_16bit_d128_pingpong_kernel_ragged(N, causal, dtype):
-    # head dimension 128 from 1024 keys on (causal: above 2048) runs the eight-wave ping-pong kernel
+    # head dimension 128 above 640 keys (causal: above 1408) runs the eight-wave ping-pong kernel
     # with its own staging ring and 256-row query tiles: whole and ragged tiles, ragged key blocks,
     # a single query tile with all four staged blocks in use, and the causal diagonal
     B, H = (1, 2) if causal else (2, 2)
