@@ -10,6 +10,7 @@ batch, halved when causal).  Prints one JSON line.
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,6 +22,7 @@ SEQLENS = (512, 1024, 2048, 4096, 8192, 16384)
 HEAD_DIM = 128
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 PEAK_FP8_TFLOPS = 5000.0
+PEAK_HBM_BYTES_PER_S = 8.0e12  # published HBM3E bandwidth
 # HBM bytes per launch of the dominant kernel (the ping-pong non-causal d=128 kernel, which serves
 # seqlen 1k..16k: average over those five shapes), from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
 # summarised in profiles/fa_fwd_bf16_d128_hbm_traffic.txt (copy-kernel calibration factors 2.000
@@ -146,12 +148,38 @@ def main():
                 "kernel": "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>",
                 "avg_launch_ms": round(dur_ms / n_launch, 4), "launches": n_launch}
 
+    # per launch: mean and median over the timed steps, and the compulsory HBM traffic (Q, K, V read, O and L
+    # written once) as a fraction of the 8 TB/s peak: the short launches sit close to that second roofline
     points = {}
     for (N, causal), ms_list in sorted(per_point.items()):
         ms = sum(ms_list) / len(ms_list)
         B, H = inputs.benchmark_shape(N, d)
+        hbm_bytes = 4 * B * H * N * d * 2 + 4 * B * H * N
         points[f"N{N}_{'causal' if causal else 'full'}"] = {
-            "ms": round(ms, 4), "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1)}
+            "ms": round(ms, 4), "median_ms": round(statistics.median(ms_list), 4),
+            "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1),
+            "hbm_frac": round(hbm_bytes / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S, 3)}
+
+    # the step's working set (257 MiB per shape) is about the size of the last-level cache: one figure with the
+    # caches flushed by a 1 GiB fill before every launch, at the shortest shape, where it matters most
+    cold = {}
+    N, B, H, q, k, v, o, lse = work[0]
+    flush = torch.empty(1 << 30, device=dev, dtype=torch.uint8)
+    for causal in (False, True):
+        ms_list = []
+        for _ in range(10):
+            flush.fill_(1)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            binding.fa_fwd(q, k, v, scale, causal, o=o, lse=lse)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms_list.append(e0.elapsed_time(e1))
+        ms = statistics.median(ms_list)
+        cold[f"N{N}_{'causal' if causal else 'full'}"] = {
+            "median_ms": round(ms, 4), "tflops": round(binding.attention_flops(B, H, N, d, causal) / ms / 1e9, 1),
+            "hbm_frac": round((4 * B * H * N * d * 2 + 4 * B * H * N) / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S, 3)}
+    del flush
 
     out = {
         "metric": "fwd attention TFLOPs/s bf16, hdim 128, seqlen 512-16k (causal + non-causal sweep aggregate)",
@@ -163,6 +191,7 @@ def main():
         "roofline": roofline,
         "frac_of_mfma_peak": round(value / PEAK_BF16_TFLOPS, 4),
         "points": points,
+        "cold_cache": cold,
     }
     if not args.no_extra:
         out["extra"] = extra_table(torch, binding, inputs, dev)
