@@ -281,23 +281,24 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                 }
             };
 
-            // elements 2c, 2c+1 of a sub-tile: P, dS and one packed register of each
-            auto softmax_pair = [&](int sub, int c) {
-                float pv[2], dsv[2];
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    const int rr = 2 * c + e, g = rr >> 2, r = rr & 3;
-                    float p = fast_exp2(__builtin_fmaf(sacc[sub][rr], sc, -l4[sub][g][r]));
-                    if constexpr (MASK) {
-                        const int qi = q0 + sub * 32 + 8 * g + 4 * half + r;
-                        const bool masked = my_key >= N || (CAUSAL && my_key > qi);
-                        p = masked ? 0.f : p;
-                    }
-                    pv[e] = p;
-                    dsv[e] = p * pacc[sub][rr];
+            // elements 2c, 2c+1 of a sub-tile: P, dS and one packed register of each.  The two elements
+            // are computed in the shadows of two different MFMAs (softmax_elem after each), the pair
+            // is packed after the second.
+            float pv[8][2], dsv[8][2];  // indexed by the pair's number within its sub-tile
+            auto softmax_elem = [&](int sub, int c, int e) {
+                const int rr = 2 * c + e, g = rr >> 2, r = rr & 3;
+                float p = fast_exp2(__builtin_fmaf(sacc[sub][rr], sc, -l4[sub][g][r]));
+                if constexpr (MASK) {
+                    const int qi = q0 + sub * 32 + 8 * g + 4 * half + r;
+                    const bool masked = my_key >= N || (CAUSAL && my_key > qi);
+                    p = masked ? 0.f : p;
                 }
-                pa[sub][c >> 2][c & 3] = E::pack2(pv[0], pv[1]);
-                dsa[sub][c >> 2][c & 3] = E::pack2(dsv[0], dsv[1]);
+                pv[c][e] = p;
+                dsv[c][e] = p * pacc[sub][rr];
+            };
+            auto softmax_pack = [&](int sub, int c) {
+                pa[sub][c >> 2][c & 3] = E::pack2(pv[c][0], pv[c][1]);
+                dsa[sub][c >> 2][c & 3] = E::pack2(dsv[c][0], dsv[c][1]);
             };
 
             // ---- stages 1 and 2: S = Q_i K_j^T, dP = dO_i V_j^T
@@ -319,30 +320,42 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                         ado[u % KP] = lds_load_16B(row_addr(u + KP) + DO_DIST);
                     }
                     if (u == KS - 2) init_dp(1);
+                    // A wave issues in order and its second MFMA waits for the matrix pipe to take it:
+                    // vector work placed after both MFMAs of a step runs in the shadow of the second
+                    // one only.  Half of it goes between the two.
                     if constexpr (VACC) {
                         if (ks == 0) MfmaVgprAcc<Tag>::first(sacc[sub], a0, kreg[ks]);
                         else MfmaVgprAcc<Tag>::run(sacc[sub], a0, kreg[ks]);
-                        MfmaVgprAcc<Tag>::run(pacc[sub], a1, vreg[ks]);
                     } else {
                         sacc[sub] = E::mma(a0, kreg[ks], ks == 0 ? zero : sacc[sub]);
-                        pacc[sub] = E::mma(a1, vreg[ks], pacc[sub]);
                     }
-                    if (sub == 0 && ks == KS - 1) fetch_l(0, 0);
                     if (sub == 1) {
                         // sub-tile 0's results were written by MFMAs the hazard checker cannot see
                         if constexpr (VACC) {
                             if (ks == 0) mfma_result_wait(sacc[0], pacc[0]);
                         }
-                        // the 8 register pairs of sub-tile 0 spread over the KS steps; the L group
-                        // of a pair is fetched one step before the step that needs it first
-                        // pair c runs at step c KS / 8
+                        // the 8 register pairs of sub-tile 0 spread over the KS steps (pair c runs at
+                        // step c KS / 8); the L group of a pair is fetched one step before the step
+                        // that needs it first
 #pragma unroll
                         for (int g = 1; g < 4; ++g)
                             if ((2 * g * KS) / 8 == ks + 1) fetch_l(0, g);
                         if (ks == KS - 1) fetch_l(1, 0);
 #pragma unroll
                         for (int c = 0; c < 8; ++c)
-                            if ((c * KS) / 8 == ks) softmax_pair(0, c);
+                            if ((c * KS) / 8 == ks) softmax_elem(0, c, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (VACC) MfmaVgprAcc<Tag>::run(pacc[sub], a1, vreg[ks]);
+                    else pacc[sub] = E::mma(a1, vreg[ks], pacc[sub]);
+                    if (sub == 0 && ks == KS - 1) fetch_l(0, 0);
+                    if (sub == 1) {
+#pragma unroll
+                        for (int c = 0; c < 8; ++c)
+                            if ((c * KS) / 8 == ks) {
+                                softmax_elem(0, c, 1);
+                                softmax_pack(0, c);
+                            }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -379,17 +392,25 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
                         qhi[w] = lds_read_tr16(tr_addr(u + KP, 1));
                     }
                     dvacc[dt] = E::mma(pa[sub][s2], b, dvacc[dt]);
-                    dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
+                    constexpr int PP = 8 / (2 * DT);
                     if (sub == 0) {
                         if constexpr (VACC) {
                             if (u == 0) mfma_result_wait(sacc[1], pacc[1]);
                         }
-                        constexpr int PP = 8 / (2 * DT);
 #pragma unroll
                         for (int g = 1; g < 4; ++g)
                             if ((2 * g) / PP == u + 1) fetch_l(1, g);
 #pragma unroll
-                        for (int p = 0; p < PP; ++p) softmax_pair(1, u * PP + p);
+                        for (int p = 0; p < PP; ++p) softmax_elem(1, u * PP + p, 0);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    dkacc[dt] = E::mma(dsa[sub][s2], b2, dkacc[dt]);
+                    if (sub == 0) {
+#pragma unroll
+                        for (int p = 0; p < PP; ++p) {
+                            softmax_elem(1, u * PP + p, 1);
+                            softmax_pack(1, u * PP + p);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
