@@ -114,3 +114,13 @@ def test_mfma_hazard_checker_finds_planted_early_access():
     assert len(hz.check(head + "\ts_nop 7\n\tv_mfma_f32_32x32x16_bf16 a[0:15], v[16:19], v[8:11], a[0:15]\n")) == 1
     # an MFMA the compiler scheduled itself (no ASMSTART) is the compiler's business
     assert hz.check("_Z6kernelv:\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], 0\n" + read) == []
+
+
+def test_bench_refuses_more_than_one_gpu_with_a_message():
+    # the build measures one GPU; the benchmark says so instead of printing a line for several
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
