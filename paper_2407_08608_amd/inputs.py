@@ -38,6 +38,19 @@ def qkv(seed, B, H, N, d, dtype="bf16", heavy_tailed=False):
     return tuple(make(seed, n, (B, H, N, d), dtype) for n in ("q", "k", "v"))
 
 
+def rising_maximum_qkv(seed, B, H, N, d, dtype="bf16", top_nats=80.0, beta=30.0):
+    """An adversarial case for online softmax: with scale d^-1/2 the score of query i and key j is
+    about top_nats * j / N plus N(0, ~3) noise, so every row's running maximum keeps rising from the
+    first key block to the last.  q = g + beta u, k_j = h_j + (top_nats sqrt(d) j / (N beta)) u with
+    g, h i.i.d. N(0,1) and u the unit vector along (1, ..., 1); v i.i.d. N(0,1)."""
+    q, k, v = (normal_tensor(seed, n, (B, H, N, d), "f32") for n in ("q", "k", "v"))
+    u = torch.full((d,), float(d) ** -0.5)
+    ramp = torch.arange(N, dtype=torch.float32) * (top_nats * float(d) ** 0.5 / (N * beta))
+    q = q + beta * u
+    k = k + ramp[:, None] * u
+    return tuple(t.to(_TORCH_DTYPES[dtype]) for t in (q, k, v))
+
+
 def random_signs(seed, d):
     """The +-1 diagonal of the incoherent-processing matrix, int8 [d]."""
     s = _rng(seed, "signs").integers(0, 2, size=d) * 2 - 1

@@ -82,7 +82,8 @@ def test_bwd_is_repeatable_and_workspace_checked():
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("N,d", [(1024, 128), (4096, 128), (16384, 128), (4096, 64), (16384, 64), (4096, 256)])
+@pytest.mark.parametrize("N,d", [(1024, 128), (4096, 128), (16384, 128), (4096, 64), (16384, 64), (4096, 256),
+                                 (16384, 256)])
 def test_bwd_benchmark_shapes_sampled_heads(N, d, causal):
     # 16k tokens, hidden size 2048 (16 heads of dim 128 or 32 of dim 64); the oracle differentiates
     # whole (batch, head) slices

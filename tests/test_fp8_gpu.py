@@ -4,11 +4,12 @@ Pre-pass: codes are bytes and scales are fp32 values decided by fp32 arithmetic 
 oracle reproduces step by step, so both must match bit for bit.
 
 Forward, against the model oracle (fp64 attention on the de-quantised tensors): the only
-rounding the kernel adds is P~ -> e4m3 (relative error <= 2^-4 per entry; the output is a
-P-weighted mean of V rows, so |dO| <= 2^-4 max|V^|) and the bf16 store (2^-9 |O|); the
-statistical estimate for N(0,1) inputs is 2^-4/sqrt(3) / sqrt(N/e) per entry,
-about 4e-3 at N=256 non-causal and 9e-3 causal.  L is computed in fp32 from exact fp8
-products and must agree to 2e-3.
+rounding the kernel adds is P~ -> e4m3 (at most 2^-4 of a normal P~, 2^-10 for a subnormal one)
+and the bf16 store (2^-9 |O|).  Every output element is held to the bound that follows for its
+own row (helpers.fp8_rounding_bound: 2^-4 of the P-weighted mean of |V^| over the keys the row
+sees, plus the subnormal floor), on N(0,1) inputs and on the heavy-tailed inputs of the paper's
+error study, where the lazily raised reference maximum and the accumulator rescale fire often.
+L is computed in fp32 from exact fp8 products and must agree to 2e-3.
 
 Forward, against the true fp64 attention on the original inputs (the paper's error study,
 section 4.3): block quantisation + incoherent processing must beat per-tensor scaling on
@@ -20,7 +21,7 @@ import torch
 
 import oracle
 from oracle import fp8_oracle as f8
-from helpers import f64, gpu_rows, max_abs, rmse
+from helpers import check_fp8_against_model_oracle, f64, gpu_rows, max_abs, rmse
 from paper_2407_08608_amd import binding, inputs
 
 pytestmark = pytest.mark.gpu
@@ -77,8 +78,19 @@ def test_quant_single_row_and_full_benchmark_block_count():
         assert scales[0, h, t] == s_ref[0, 0, 0]
 
 
+_PREPARED = {}  # the last problem prepared: consecutive cases differ in the mask only
+
+
 def _prepare(seed, B, H, N, d, heavy, use_signs=True, per_tensor=False):
     """Quantise with the ORACLE (inputs to the kernel under test never come from the HIP path)."""
+    key = (seed, B, H, N, d, heavy, use_signs, per_tensor)
+    if key not in _PREPARED:
+        _PREPARED.clear()
+        _PREPARED[key] = _prepare_uncached(*key)
+    return _PREPARED[key]
+
+
+def _prepare_uncached(seed, B, H, N, d, heavy, use_signs, per_tensor):
     q, k, v = inputs.qkv(seed, B, H, N, d, "bf16", heavy_tailed=heavy)
     signs = inputs.random_signs(seed, d).numpy() if use_signs else None
     qc, qs = f8.quantize(q.float().numpy(), signs, 128, per_tensor)
@@ -94,36 +106,27 @@ def _fwd_fp8_gpu(codes, scales, scale, causal):
     return o, lse
 
 
+@pytest.mark.parametrize("heavy", [False, True])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("d", [64, 128, 256])
 @pytest.mark.parametrize("N", [1, 100, 256, 700, 1500])
-def test_fp8_forward_matches_model_oracle(N, d, causal):
+def test_fp8_forward_matches_model_oracle(N, d, causal, heavy):
     # 1500 keys: past the length up to which d = 128 keeps its four-wave tile, with a ragged tail
     B, H = 2, 2
-    _, codes, scales = _prepare(30 + N + d, B, H, N, d, heavy=False)
+    # heavy: the inputs of the paper's error study (section 4.3), N(0,1) + N(0,100) Bernoulli(0.001)
+    _, codes, scales = _prepare(30 + N + d, B, H, N, d, heavy=heavy)
     scale = d ** -0.5
     o, lse = _fwd_fp8_gpu(codes, scales, scale, causal)
-    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
-    o_ref, l_ref = oracle.attention_fwd(*deq, scale, causal)
-    bound = 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
-    assert np.isfinite(f64(o)).all()
-    assert max_abs(f64(o), o_ref) <= bound
-    if N >= 256:
-        assert rmse(f64(o), o_ref) <= 1.5e-2
-    assert max_abs(f64(lse), l_ref) <= 2e-3
+    check_fp8_against_model_oracle(o, lse, codes, scales, scale, causal)
 
 
-def test_fp8_forward_d64_eight_wave_tile_ragged():
+@pytest.mark.parametrize("heavy", [False, True])
+def test_fp8_forward_d64_eight_wave_tile_ragged(heavy):
     # d = 64 without a mask switches to its 256-query tile only above 3072 keys
     B, H, N, d = 1, 2, 3300, 64
-    _, codes, scales = _prepare(39, B, H, N, d, heavy=False)
+    _, codes, scales = _prepare(39, B, H, N, d, heavy=heavy)
     o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, False)
-    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
-    o_ref, l_ref = oracle.attention_fwd(*deq, d ** -0.5, False)
-    assert np.isfinite(f64(o)).all()
-    assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
-    assert rmse(f64(o), o_ref) <= 1.5e-2
-    assert max_abs(f64(lse), l_ref) <= 2e-3
+    check_fp8_against_model_oracle(o, lse, codes, scales, d ** -0.5, False)
 
 
 def test_fp8_forward_block_scales_really_differ_per_block():
@@ -138,17 +141,14 @@ def test_fp8_forward_block_scales_really_differ_per_block():
     assert scales[1][0, 0, 3] > 2 * scales[1][0, 0, 0]
     for causal in (False, True):
         o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, causal)
-        deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
-        o_ref, l_ref = oracle.attention_fwd(*deq, d ** -0.5, causal)
-        assert max_abs(f64(lse), l_ref) <= 2e-3
-        assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
+        check_fp8_against_model_oracle(o, lse, codes, scales, d ** -0.5, causal)
 
 
 @pytest.mark.parametrize("causal", [False, True])
 def test_fp8_forward_v_scales_jump_up_and_down_by_large_factors(causal):
-    # the kernel keeps its accumulator in units of a reference V scale that it moves only on large
-    # jumps: make consecutive V blocks differ by factors far outside and inside that band, with an
-    # all-zero block (scale 1 by convention) in the middle
+    # a V block's scale enters the kernel as an offset in the exponent of P~, and the reference maximum
+    # is taken over the offset scores: make consecutive V blocks differ by factors far above and below
+    # the lazy-raise threshold, with an all-zero block (scale 1 by convention) in the middle
     B, H, N, d = 1, 2, 1024, 128
     q, k, v = inputs.qkv(42, B, H, N, d, "bf16")
     for t, f in enumerate([1.0, 64.0, 0.02, 0.0, 3.0, 1.5, 0.001, 200.0]):
@@ -156,15 +156,19 @@ def test_fp8_forward_v_scales_jump_up_and_down_by_large_factors(causal):
     codes, scales = zip(*[f8.quantize(x.float().numpy(), None, 128) for x in (q, k, v)])
     assert scales[2][0, 0, 3] == 1.0 and scales[2][0, 0, 1] > 30 * scales[2][0, 0, 0]
     o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, causal)
-    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
-    o_ref, l_ref = oracle.attention_fwd(*deq, d ** -0.5, causal)
-    assert np.isfinite(f64(o)).all()
-    assert max_abs(f64(lse), l_ref) <= 2e-3
-    # per row: P~ rounding is 2^-4 relative on every term, so the error is bounded by 2^-4 of the
-    # P-weighted mean of |V^| over the keys the row sees (plus the bf16 store)
-    p_abs, _ = oracle.attention_fwd(deq[0], deq[1], np.abs(deq[2]), d ** -0.5, causal)
-    err = np.abs(f64(o) - o_ref)
-    assert (err <= 2.0 ** -4 * 1.05 * p_abs + 2.0 ** -8 * np.abs(o_ref) + 1e-6).all()
+    check_fp8_against_model_oracle(o, lse, codes, scales, d ** -0.5, causal)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(2300, 128), (2300, 256), (3300, 64), (600, 128)])
+def test_fp8_row_maxima_that_rise_block_after_block(N, d, causal):
+    # scores grow from ~0 at the first key to ~80 at the last, so the reference maximum (threshold 2 in
+    # log2 units) rises in almost every key block; the d = 256 kernel applies the rescale one block
+    # behind the scores
+    q, k, v = inputs.rising_maximum_qkv(44, 1, 2, N, d, "bf16")
+    codes, scales = zip(*[f8.quantize(x.float().numpy(), None, 128) for x in (q, k, v)])
+    o, lse = _fwd_fp8_gpu(codes, scales, d ** -0.5, causal)
+    check_fp8_against_model_oracle(o, lse, codes, scales, d ** -0.5, causal)
 
 
 @pytest.mark.parametrize("causal", [False, True])
@@ -178,10 +182,8 @@ def test_fp8_unit_scale_entry_point_matches_oracle(d, causal):
     dev = [torch.from_numpy(c).cuda() for c in (qc, kc, vc)]
     o, lse = binding.fa_fwd(*dev, d ** -0.5, causal, dtype=binding.FA_FP8_E4M3)
     torch.cuda.synchronize()
-    vd = f8.e4m3_decode(vc)
-    o_ref, l_ref = oracle.attention_fwd(f8.e4m3_decode(qc), f8.e4m3_decode(kc), vd, d ** -0.5, causal)
-    assert max_abs(f64(o), o_ref) <= 2.0 ** -4 * np.abs(vd).max() * 1.05 + 2.0 ** -7
-    assert max_abs(f64(lse), l_ref) <= 2e-3
+    ones = np.ones((B, H, -(-N // 128)), dtype=np.float32)
+    check_fp8_against_model_oracle(o, lse, (qc, kc, vc), (ones, ones, ones), d ** -0.5, causal)
 
 
 def test_fp8_unit_scale_entry_point_and_constant_values():
@@ -201,32 +203,34 @@ def test_fp8_unit_scale_entry_point_and_constant_values():
 
 
 @pytest.mark.parametrize("causal", [False, True])
-@pytest.mark.parametrize("H,N,d", [(16, 16384, 128), (8, 16384, 256), (32, 16384, 64), (16, 4096, 128)])
-def test_fp8_benchmark_shapes_sampled_rows(H, N, d, causal):
+@pytest.mark.parametrize("H,N,d,heavy", [(16, 16384, 128, False), (8, 16384, 256, False), (32, 16384, 64, False),
+                                         (16, 4096, 128, False), (16, 16384, 128, True), (8, 16384, 256, True),
+                                         (32, 16384, 64, True), (16, 4096, 128, True), (8, 4096, 256, True)])
+def test_fp8_benchmark_shapes_sampled_rows(H, N, d, heavy, causal):
     """The shapes the benchmark times (section 4.1: 16k tokens in total, hidden size 2048), in the
-    kernel and launch configuration it times; sampled output rows against the model oracle."""
+    kernel and launch configuration it times, on N(0,1) inputs and on the heavy-tailed inputs of the
+    error study (section 4.3); sampled output rows against the model oracle, element by element."""
     B = 16384 // N
-    _, codes, scales = _prepare(70 + d, B, H, N, d, heavy=False)
+    _, codes, scales = _prepare(70 + d, B, H, N, d, heavy=heavy)
     scale = d ** -0.5
     o, lse = _fwd_fp8_gpu(codes, scales, scale, causal)
     assert bool(torch.isfinite(o).all()) and bool(torch.isfinite(lse).all())
-    deq = [f8.dequantize(c, s, 128) for c, s in zip(codes, scales)]
     rows = inputs.sample_rows(71 + d, B * H * N, 384)
     # the first and the last rows of a head, and both sides of a 128-row scale block boundary
     rows = np.unique(np.concatenate([rows, [0, 1, 127, 128, N - 1, N, B * H * N - 1]])).astype(np.int64)
-    o_ref, l_ref = oracle.attention_fwd_rows(*deq, rows, scale, causal)
-    got = gpu_rows(o, rows)
-    assert max_abs(got, o_ref) <= 2.0 ** -4 * np.abs(deq[2]).max() * 1.05 + 2.0 ** -7
+    got, o_ref = check_fp8_against_model_oracle(o, lse, codes, scales, scale, causal, rows=rows)
     # long rows average the P~ rounding down; causal rows are as short as one key
-    assert rmse(got, o_ref) <= (8e-3 if causal else 2e-3)
-    assert max_abs(gpu_rows(lse, rows), l_ref) <= 2e-3
+    if not heavy:
+        assert rmse(got, o_ref) <= (8e-3 if causal else 2e-3)
 
 
 @pytest.mark.parametrize("causal", [False, True])
-def test_fp8_error_ordering_on_heavy_tailed_inputs_full_gpu_path(causal):
+@pytest.mark.parametrize("N,d", [(4096, 128), (4096, 256), (16384, 128), (16384, 256), (4096, 64)])
+def test_fp8_error_ordering_on_heavy_tailed_inputs_full_gpu_path(N, d, causal):
     """Section 4.3 / Table 3: quantisation pre-pass and forward both on the GPU, error against
-    fp64 attention on the original inputs; d=128, N=4096 point of the sweep, sampled rows."""
-    B, H, N, d = 4, 16, 4096, 128
+    fp64 attention on the original inputs, at points of the sweep (16k tokens, hidden size 2048);
+    sampled rows."""
+    B, H = inputs.benchmark_shape(N, d)
     q, k, v = inputs.qkv(50, B, H, N, d, "bf16", heavy_tailed=True)
     signs = inputs.random_signs(50, d).cuda()
     qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
@@ -247,7 +251,7 @@ def test_fp8_error_ordering_on_heavy_tailed_inputs_full_gpu_path(causal):
     baseline = run(None, True)
     no_block = run(signs, True)
     no_incoh = run(None, False)
-    print(f"fp8 rmse causal={causal}: full={full:.3e} baseline={baseline:.3e} "
+    print(f"fp8 rmse N={N} d={d} causal={causal}: full={full:.3e} baseline={baseline:.3e} "
           f"no_block_quant={no_block:.3e} no_incoherent={no_incoh:.3e}")
     assert full < baseline
     assert full < 5e-2

@@ -117,6 +117,16 @@ def test_bf16_large_scores_stay_finite():
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N,d", [(2300, 128), (2300, 256), (2300, 64), (600, 128)])
+def test_bf16_row_maxima_that_rise_block_after_block(N, d, causal):
+    # scores grow from ~0 at the first key to ~80 at the last: the lazily raised reference maximum must
+    # move (and O, l be rescaled) a dozen times per row; the ping-pong (d = 128) and pipelined (d = 256)
+    # kernels compute that rescale one block behind the scores
+    q, k, v = inputs.rising_maximum_qkv(8, 1, 2, N, d, "bf16")
+    _check_full(q, k, v, d ** -0.5, causal, o_tol=4e-2, r_tol=6e-3, l_tol=5e-2)
+
+
+@pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("N,d", [(16384, 128), (4096, 128), (512, 128), (16384, 64), (8192, 256)])
 def test_bf16_benchmark_shapes_sampled_rows(N, d, causal):
     # the paper's sweep: 16k tokens, hidden 2048; rows are independent, so the oracle checks a sample
