@@ -46,7 +46,8 @@ typedef enum {
     FA_ERR_UNSUPPORTED = 4, /* a valid request this build has no kernel for (e.g. head dim 96) */
     FA_ERR_ALIGN = 5,       /* a tensor pointer is not 16-byte aligned */
     FA_ERR_WORKSPACE = 6,   /* workspace NULL or smaller than fa_bwd_workspace_bytes() */
-    FA_ERR_LAUNCH = 7       /* the HIP runtime rejected a launch */
+    FA_ERR_LAUNCH = 7,      /* the HIP runtime rejected a launch */
+    FA_ERR_TOO_LARGE = 8    /* fa_bwd_noalloc: B*H*N exceeds FA_BWD_NOALLOC_MAX_ROWS */
 } fa_status;
 
 typedef enum {
@@ -122,6 +123,28 @@ size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype);
 int fa_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse,
            const void* dout, void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes,
            int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
+
+/*
+ * fa_bwd for callers that cannot allocate or hand over device scratch: code running under HIP
+ * graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same
+ * operation, arguments, kernels and results (bit for bit) as fa_bwd, but the D vector lives in a
+ * fixed device array inside the library instead of a caller workspace; the call allocates and frees
+ * nothing.
+ *   - Limit: B*H*N <= FA_BWD_NOALLOC_MAX_ROWS (4 MiB of scratch per GPU, held by every GPU the
+ *     library is used on until the process ends); larger requests return FA_ERR_TOO_LARGE and
+ *     launch nothing.
+ *   - The array is per GPU and shared by every call on that GPU: two calls that may run
+ *     concurrently on one GPU (different streams, different host threads) race on it and must be
+ *     serialised by the caller; calls on one stream are ordered and safe.  Nothing in it needs
+ *     clearing between calls (the first kernel of a call overwrites what the others read).
+ *   - The array's device address is looked up once per GPU on the first call made with that GPU
+ *     current; if that lookup fails the call returns FA_ERR_LAUNCH.
+ */
+#define FA_BWD_NOALLOC_MAX_ROWS 1048576
+
+int fa_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const float* lse,
+                   const void* dout, void* dq, void* dk, void* dv,
+                   int B, int H, int N, int d, float scale, int causal, int dtype, void* stream);
 
 /*
  * Forward pass with the kernel schedule forced, for the scheduling ablation (section 4.2,

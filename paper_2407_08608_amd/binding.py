@@ -17,7 +17,7 @@ FA_F32, FA_BF16, FA_F16, FA_FP8_E4M3 = 0, 1, 2, 3
 _DTYPE_CODE = {torch.float32: FA_F32, torch.bfloat16: FA_BF16, torch.float16: FA_F16}
 
 EXPORTS = ("fa_fwd", "fa_fwd_fp8", "fa_fp8_quant_hadamard", "fa_bwd_workspace_bytes", "fa_bwd",
-           "fa_fwd_schedule", "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
+           "fa_fwd_schedule", "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_bwd_noalloc", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
 
 _lib = None
 
@@ -55,6 +55,8 @@ def lib():
         L.fa_fwd_fp8_gqa.restype = ci
         L.fa_bwd_gqa.argtypes = [vp] * 10 + [ctypes.c_size_t, ci, ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_bwd_gqa.restype = ci
+        L.fa_bwd_noalloc.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ci, vp]
+        L.fa_bwd_noalloc.restype = ci
         L.fa_probe_mfma_flops.argtypes = [ci, ci]
         L.fa_probe_mfma_flops.restype = ctypes.c_double
         L.fa_probe_mfma.argtypes = [vp, ctypes.c_size_t, fp, ci, ci, vp]
@@ -149,6 +151,22 @@ def fa_bwd(q, k, v, o, lse, dout, scale, causal, dq=None, dk=None, dv=None, work
                       B, H, N, d, float(scale), int(bool(causal)), code, _stream())
     if st != FA_OK:
         raise FaError(st, "fa_bwd")
+    return dq, dk, dv
+
+
+FA_BWD_NOALLOC_MAX_ROWS = 1048576
+
+
+def fa_bwd_noalloc(q, k, v, o, lse, dout, scale, causal, dq, dk, dv):
+    """fa_bwd on the library's fixed scratch: the caller passes every tensor, outputs included, and the
+    call allocates nothing (neither here nor in the library)."""
+    _check_dev(q, k, v, o, lse, dout, dq, dk, dv)
+    B, H, N, d = q.shape
+    st = lib().fa_bwd_noalloc(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), dout.data_ptr(),
+                              dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), B, H, N, d, float(scale),
+                              int(bool(causal)), _DTYPE_CODE[q.dtype], _stream())
+    if st != FA_OK:
+        raise FaError(st, "fa_bwd_noalloc")
     return dq, dk, dv
 
 

@@ -3,9 +3,34 @@
 #include <math.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "fa_launch.h"
 
+// Scratch of fa_bwd_noalloc: the backward's D = rowsum(dO o O) vector.  A file-scope device array, so
+// every GPU the library runs on holds its own copy from the moment the code object is loaded until the
+// process ends, and no call ever allocates.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels and launches take the per-device address kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char fa_noalloc_scratch[FA_BWD_NOALLOC_MAX_ROWS * sizeof(float)];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Address of the scratch array on the current device (resolved once per device), or nullptr.
+void* noalloc_scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p) return p;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(fa_noalloc_scratch)) != hipSuccess || !p) {
+        (void)hipGetLastError();
+        return nullptr;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+    return p;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool head_dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
@@ -36,6 +61,7 @@ const char* fa_status_string(int status) {
         case FA_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
         case FA_ERR_WORKSPACE: return "workspace missing or too small";
         case FA_ERR_LAUNCH: return "HIP runtime rejected the launch";
+        case FA_ERR_TOO_LARGE: return "problem exceeds the fixed scratch of an entry point that cannot allocate";
         default: return "unknown status";
     }
 }
@@ -121,9 +147,10 @@ size_t fa_bwd_workspace_bytes(int B, int H, int N, int d, int dtype) {
     return fa::bwd_workspace_bytes(B, H, N, d);
 }
 
-static int bwd_any(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
-                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int H_kv, int N,
-                   int d, float scale, int causal, int dtype, void* stream) {
+// Everything about a backward request except its workspace.
+static int check_bwd(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+                     void* dq, void* dk, void* dv, int B, int H, int H_kv, int N, int d, float scale, int causal,
+                     int dtype) {
     if (!q || !k || !v || !o || !lse || !dout || !dq || !dk || !dv) return FA_ERR_NULL;
     if (dtype < FA_F32 || dtype > FA_FP8_E4M3) return FA_ERR_DTYPE;
     int st = check_common(B, H, N, d, scale, causal);
@@ -133,6 +160,14 @@ static int bwd_any(const void* q, const void* k, const void* v, const void* o, c
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse) || !aligned16(dout) ||
         !aligned16(dq) || !aligned16(dk) || !aligned16(dv))
         return FA_ERR_ALIGN;
+    return FA_OK;
+}
+
+static int bwd_any(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+                   void* dq, void* dk, void* dv, void* workspace, size_t workspace_bytes, int B, int H, int H_kv, int N,
+                   int d, float scale, int causal, int dtype, void* stream) {
+    int st = check_bwd(q, k, v, o, lse, dout, dq, dk, dv, B, H, H_kv, N, d, scale, causal, dtype);
+    if (st != FA_OK) return st;
     if (!workspace || workspace_bytes < fa::bwd_workspace_bytes(B, H, N, d)) return FA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FA_ERR_ALIGN;
     return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, d, scale, causal, dtype,
@@ -151,6 +186,19 @@ int fa_bwd_gqa(const void* q, const void* k, const void* v, const void* o, const
                int d, float scale, int causal, int dtype, void* stream) {
     return bwd_any(q, k, v, o, lse, dout, dq, dk, dv, workspace, workspace_bytes, B, H, H_kv, N, d, scale, causal,
                    dtype, stream);
+}
+
+int fa_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, const float* lse, const void* dout,
+                   void* dq, void* dk, void* dv, int B, int H, int N, int d, float scale, int causal, int dtype,
+                   void* stream) {
+    int st = check_bwd(q, k, v, o, lse, dout, dq, dk, dv, B, H, H, N, d, scale, causal, dtype);
+    if (st != FA_OK) return st;
+    if ((long)B * H * N > (long)FA_BWD_NOALLOC_MAX_ROWS) return FA_ERR_TOO_LARGE;
+    void* scratch = noalloc_scratch_on_current_device();
+    if (!scratch) return FA_ERR_LAUNCH;
+    // D is written in full by the first kernel before the others read it: nothing to clear
+    return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, scratch, B, H, H, N, d, scale, causal, dtype,
+                          static_cast<hipStream_t>(stream));
 }
 
 double fa_probe_mfma_flops(int dtype, int iters) {

@@ -69,6 +69,12 @@ def test_fp8_and_bwd_entry_points_validate():
     assert L.fa_bwd(*args) == 4
     args = [p] * 9 + [None, 0, 1, 1, 16, 128, 0.1, 0, binding.FA_BF16, None]
     assert L.fa_bwd(*args) == 6
+    # the variant on the library's fixed scratch: same checks, then its own size limit, all before any HIP call
+    na = lambda **kw: L.fa_bwd_noalloc(*[kw.get("ptr", p)] * 9, kw.get("B", 1), 1, kw.get("N", 16), kw.get("d", 128), 0.1, 0,
+                                       kw.get("dtype", binding.FA_BF16), None)
+    assert na(ptr=None) == 1 and na(d=96) == 4 and na(dtype=binding.FA_F32) == 4
+    assert na(B=4, N=binding.FA_BWD_NOALLOC_MAX_ROWS // 4 + 1, d=64) == 8
+    assert binding.status_string(8).startswith("problem exceeds")
 
 
 def test_mfma_probe_validates_and_counts_flops():
