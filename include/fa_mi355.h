@@ -166,6 +166,16 @@ int fa_fwd_schedule(const void* q, const void* k, const void* v, void* o, float*
                     void* stream);
 
 /*
+ * Which kernel serves a forward request: the name a profiler (rocprofv3 --kernel-trace) shows for
+ * the kernel that fa_fwd (dtype FA_F32 / FA_BF16 / FA_F16) or fa_fwd_fp8 (dtype FA_FP8_E4M3, the
+ * block-scaled instantiation) launches for N keys, head dimension d and this mask.  The choice
+ * depends on nothing else.  Host only: launches nothing, touches no device.  Returns a static
+ * NUL-terminated string, or NULL for a request those calls would reject.  For measurement code that
+ * must attribute launches to kernels without copying the library's thresholds.
+ */
+const char* fa_fwd_kernel_name(int dtype, int N, int d, int causal);
+
+/*
  * Multi-query / grouped-query attention (section 3.1, "Attention variants": the tensor
  * indexing changes, K and V are not duplicated in HBM).  q, o, dout, dq are [B,H,N,d] and
  * lse is [B,H,N] as above; k, v, dk, dv are [B,H_kv,N,d] (FP8: k_scale, v_scale are

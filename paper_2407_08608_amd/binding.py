@@ -17,7 +17,8 @@ FA_F32, FA_BF16, FA_F16, FA_FP8_E4M3 = 0, 1, 2, 3
 _DTYPE_CODE = {torch.float32: FA_F32, torch.bfloat16: FA_BF16, torch.float16: FA_F16}
 
 EXPORTS = ("fa_fwd", "fa_fwd_fp8", "fa_fp8_quant_hadamard", "fa_bwd_workspace_bytes", "fa_bwd",
-           "fa_fwd_schedule", "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_bwd_noalloc", "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
+           "fa_fwd_schedule", "fa_fwd_gqa", "fa_fwd_fp8_gqa", "fa_bwd_gqa", "fa_bwd_noalloc", "fa_fwd_kernel_name",
+           "fa_probe_mfma_flops", "fa_probe_mfma", "fa_status_string")
 
 _lib = None
 
@@ -57,6 +58,8 @@ def lib():
         L.fa_bwd_gqa.restype = ci
         L.fa_bwd_noalloc.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ci, vp]
         L.fa_bwd_noalloc.restype = ci
+        L.fa_fwd_kernel_name.argtypes = [ci, ci, ci, ci]
+        L.fa_fwd_kernel_name.restype = ctypes.c_char_p
         L.fa_probe_mfma_flops.argtypes = [ci, ci]
         L.fa_probe_mfma_flops.restype = ctypes.c_double
         L.fa_probe_mfma.argtypes = [vp, ctypes.c_size_t, fp, ci, ci, vp]
@@ -257,12 +260,7 @@ def fa_probe_mfma(operands, dtype, iters, sink=None):
     return sink
 
 
-def attention_flops(B, H, N, d, causal, backward=False):
-    """FLOP count by the paper's accounting (section 4.1): 4*N^2*d per head and batch element,
-    halved under a causal mask, times 2.5 for the backward pass."""
-    f = 4.0 * N * N * d * H * B
-    if causal:
-        f *= 0.5
-    if backward:
-        f *= 2.5
-    return f
+def fa_fwd_kernel_name(dtype, N, d, causal):
+    """Profiler name of the kernel that serves this forward request (None if unsupported)."""
+    name = lib().fa_fwd_kernel_name(int(dtype), int(N), int(d), int(bool(causal)))
+    return None if name is None else name.decode()

@@ -109,6 +109,17 @@ int fa_fwd_schedule(const void* q, const void* k, const void* v, void* o, float*
     return fwd_any(q, k, v, o, lse, B, H, H, N, d, scale, causal, dtype, schedule, stream);
 }
 
+const char* fa_fwd_kernel_name(int dtype, int N, int d, int causal) {
+    if (N <= 0 || (causal != 0 && causal != 1)) return nullptr;
+    switch (dtype) {
+        case FA_F32: return d == 64 ? (causal ? "fa_fwd_f32_kernel<64, 32, true>" : "fa_fwd_f32_kernel<64, 32, false>") : nullptr;
+        case FA_BF16: return fa::fwd_16bit_kernel_name(false, N, d, causal);
+        case FA_F16: return fa::fwd_16bit_kernel_name(true, N, d, causal);
+        case FA_FP8_E4M3: return fa::fwd_fp8_kernel_name(N, d, causal);
+        default: return nullptr;
+    }
+}
+
 int fa_fwd_gqa(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,
                float scale, int causal, int dtype, void* stream) {
     return fwd_any(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, dtype, FA_SCHED_AUTO, stream);

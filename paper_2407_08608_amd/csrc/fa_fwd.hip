@@ -1057,6 +1057,16 @@ static int launch_d256(const void* q, const void* k, const void* v, void* o, flo
 //     four waves for short problems (crossover near 700 keys without a mask, 1300 with one).
 //   d = 256: the 128-register output accumulator allows only one wave per SIMD; fa_fwd_d256_kernel
 //     pipelines the softmax of one block under the score MFMAs of the next inside that wave.
+enum class Fwd16 { kTile4, kTile8, kPingPong, kD256, kNone };
+static Fwd16 choose_16bit(int d, int N, int causal) {
+    switch (d) {
+        case 64: return N <= (causal ? 1280 : 640) ? Fwd16::kTile4 : Fwd16::kTile8;
+        case 128: return N <= (causal ? 1408 : 640) ? Fwd16::kTile4 : Fwd16::kPingPong;
+        case 256: return Fwd16::kD256;
+        default: return Fwd16::kNone;
+    }
+}
+
 template <typename Tag>
 static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N,
                           int d, float scale, int causal, int schedule, hipStream_t stream) {
@@ -1072,17 +1082,41 @@ static int dispatch_16bit(const void* q, const void* k, const void* v, void* o, 
             default: return FA_ERR_SHAPE;
         }
     }
-    switch (d) {
-        case 64:
-            if (N <= (causal ? 1280 : 640)) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-            return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 128:
-            if (N <= (causal ? 1408 : 640))
-                return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-            return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256: return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+    switch (choose_16bit(d, N, causal)) {
+        case Fwd16::kTile4:
+            if (d == 64) return launch_16bit<Tag, 64, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+            return launch_16bit<Tag, 128, 64, 4, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case Fwd16::kTile8: return launch_16bit<Tag, 64, 64, 8, 1, 0>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case Fwd16::kPingPong: return launch_pingpong<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
+        case Fwd16::kD256: return launch_d256<Tag>(q, k, v, o, lse, B, H, H_kv, N, scale, causal, stream);
         default: return FA_ERR_UNSUPPORTED;
     }
+}
+
+// The name a profiler shows for the kernel dispatch_16bit picks (FA_SCHED_AUTO).
+const char* fwd_16bit_kernel_name(bool f16, int N, int d, int causal) {
+    static const char* const names[2][2][5] = {
+        {{"fa_fwd_16bit_kernel<bf16_tag, 64, 64, 4, 1, 0, false>", "fa_fwd_16bit_kernel<bf16_tag, 128, 64, 4, 1, 0, false>",
+          "fa_fwd_16bit_kernel<bf16_tag, 64, 64, 8, 1, 0, false>", "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>",
+          "fa_fwd_d256_kernel<bf16_tag, false>"},
+         {"fa_fwd_16bit_kernel<bf16_tag, 64, 64, 4, 1, 0, true>", "fa_fwd_16bit_kernel<bf16_tag, 128, 64, 4, 1, 0, true>",
+          "fa_fwd_16bit_kernel<bf16_tag, 64, 64, 8, 1, 0, true>", "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, true>",
+          "fa_fwd_d256_kernel<bf16_tag, true>"}},
+        {{"fa_fwd_16bit_kernel<f16_tag, 64, 64, 4, 1, 0, false>", "fa_fwd_16bit_kernel<f16_tag, 128, 64, 4, 1, 0, false>",
+          "fa_fwd_16bit_kernel<f16_tag, 64, 64, 8, 1, 0, false>", "fa_fwd_pingpong_kernel<f16_tag, 64, 4, false>",
+          "fa_fwd_d256_kernel<f16_tag, false>"},
+         {"fa_fwd_16bit_kernel<f16_tag, 64, 64, 4, 1, 0, true>", "fa_fwd_16bit_kernel<f16_tag, 128, 64, 4, 1, 0, true>",
+          "fa_fwd_16bit_kernel<f16_tag, 64, 64, 8, 1, 0, true>", "fa_fwd_pingpong_kernel<f16_tag, 64, 4, true>",
+          "fa_fwd_d256_kernel<f16_tag, true>"}}};
+    int idx;
+    switch (choose_16bit(d, N, causal)) {
+        case Fwd16::kTile4: idx = d == 64 ? 0 : 1; break;
+        case Fwd16::kTile8: idx = 2; break;
+        case Fwd16::kPingPong: idx = 3; break;
+        case Fwd16::kD256: idx = 4; break;
+        default: return nullptr;
+    }
+    return names[f16 ? 1 : 0][causal ? 1 : 0][idx];
 }
 
 int launch_fwd_bf16(const void* q, const void* k, const void* v, void* o, float* lse, int B, int H, int H_kv, int N, int d,

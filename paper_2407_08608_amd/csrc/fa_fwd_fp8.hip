@@ -659,24 +659,53 @@ static int launch_fp8(const void* q8, const void* k8, const void* v8, const floa
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;
 }
 
+enum class FwdFp8 { kTile4, kTile8, kPipe256, kNone };
+static FwdFp8 choose_fp8(int d, int N, int causal) {
+    // Short problems keep the 128-row tile of four waves (more workgroups, less waste on the diagonal); the
+    // crossovers were measured on block-scaled inputs at 16k tokens per launch.
+    switch (d) {
+        case 64: return (causal || N <= 3072) ? FwdFp8::kTile4 : FwdFp8::kTile8;
+        // (fa_fwd_fp8_pipe_kernel<128, 8>, two waves per SIMD, is correct and measured 5 % slower than the 8-wave tile)
+        case 128: return N <= (causal ? 1280 : 704) ? FwdFp8::kTile4 : FwdFp8::kTile8;
+        case 256: return FwdFp8::kPipe256;
+        default: return FwdFp8::kNone;
+    }
+}
+
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
                    const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d, float scale, int causal,
                    hipStream_t stream) {
-    switch (d) {
-        // Short problems keep the 128-row tile of four waves (more workgroups, less waste on the diagonal); the
-        // crossovers were measured on block-scaled inputs at 16k tokens per launch.
-        case 64:
-            if (causal || N <= 3072)
-                return launch_fp8<64, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-            return launch_fp8<64, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 128:
-            if (N <= (causal ? 1280 : 704))
-                return launch_fp8<128, 64, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-            // (fa_fwd_fp8_pipe_kernel<128, 8>, two waves per SIMD, is correct and measured 5 % slower than this)
-            return launch_fp8<128, 128, 8>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
-        case 256: return launch_fp8_pipe<256, 4>(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream);
+#define FA_FP8_ARGS q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, scale, causal, stream
+    switch (choose_fp8(d, N, causal)) {
+        case FwdFp8::kTile4:
+            if (d == 64) return launch_fp8<64, 64, 4>(FA_FP8_ARGS);
+            return launch_fp8<128, 64, 4>(FA_FP8_ARGS);
+        case FwdFp8::kTile8:
+            if (d == 64) return launch_fp8<64, 128, 8>(FA_FP8_ARGS);
+            return launch_fp8<128, 128, 8>(FA_FP8_ARGS);
+        case FwdFp8::kPipe256: return launch_fp8_pipe<256, 4>(FA_FP8_ARGS);
         default: return FA_ERR_UNSUPPORTED;
     }
+#undef FA_FP8_ARGS
+}
+
+// The name a profiler shows for the kernel launch_fwd_fp8 picks (block-scaled instantiation).
+const char* fwd_fp8_kernel_name(int N, int d, int causal) {
+    static const char* const names[2][5] = {
+        {"fa_fwd_fp8_kernel<64, 64, 4, false, true>", "fa_fwd_fp8_kernel<128, 64, 4, false, true>",
+         "fa_fwd_fp8_kernel<64, 128, 8, false, true>", "fa_fwd_fp8_kernel<128, 128, 8, false, true>",
+         "fa_fwd_fp8_pipe_kernel<256, 4, false, true>"},
+        {"fa_fwd_fp8_kernel<64, 64, 4, true, true>", "fa_fwd_fp8_kernel<128, 64, 4, true, true>",
+         "fa_fwd_fp8_kernel<64, 128, 8, true, true>", "fa_fwd_fp8_kernel<128, 128, 8, true, true>",
+         "fa_fwd_fp8_pipe_kernel<256, 4, true, true>"}};
+    int idx;
+    switch (choose_fp8(d, N, causal)) {
+        case FwdFp8::kTile4: idx = d == 64 ? 0 : 1; break;
+        case FwdFp8::kTile8: idx = d == 64 ? 2 : 3; break;
+        case FwdFp8::kPipe256: idx = 4; break;
+        default: return nullptr;
+    }
+    return names[causal ? 1 : 0][idx];
 }
 
 }  // namespace fa

@@ -18,6 +18,8 @@ int launch_fwd_f32(const void* q, const void* k, const void* v, void* o, float* 
 int launch_fwd_fp8(const void* q8, const void* k8, const void* v8, const float* q_scale, const float* k_scale,
                    const float* v_scale, void* o, float* lse, int B, int H, int H_kv, int N, int d, float scale, int causal,
                    hipStream_t stream);
+const char* fwd_16bit_kernel_name(bool f16, int N, int d, int causal);
+const char* fwd_fp8_kernel_name(int N, int d, int causal);
 int launch_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales, int B, int H, int N, int d,
                           const signed char* signs, int per_tensor, hipStream_t stream);
 size_t bwd_workspace_bytes(int B, int H, int N, int d);

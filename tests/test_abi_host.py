@@ -6,6 +6,7 @@ import re
 
 import pytest
 
+import bench
 from paper_2407_08608_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -77,6 +78,24 @@ def test_fp8_and_bwd_entry_points_validate():
     assert binding.status_string(8).startswith("problem exceeds")
 
 
+def test_kernel_name_query_follows_the_launcher():
+    # the benchmark attributes launches to kernels through this call; every request the forward accepts has a name
+    name = binding.fa_fwd_kernel_name
+    for dtype in (binding.FA_BF16, binding.FA_F16, binding.FA_FP8_E4M3):
+        for d in (64, 128, 256):
+            for N in (1, 512, 640, 641, 704, 705, 1280, 1281, 1408, 1409, 3072, 3073, 16384):
+                for causal in (False, True):
+                    n = name(dtype, N, d, causal)
+                    assert n and n.startswith("fa_fwd_") and ("true" if causal else "false") in n
+    assert name(binding.FA_F32, 256, 64, False) == "fa_fwd_f32_kernel<64, 32, false>"
+    assert name(binding.FA_F32, 256, 128, False) is None and name(binding.FA_BF16, 256, 96, False) is None
+    assert name(binding.FA_BF16, 0, 128, False) is None and name(9, 16, 128, False) is None
+    # every kernel the benchmark holds a measured HBM-traffic figure for is one the launcher can still choose
+    sweep = {name(dt, N, 128, c) for dt in (binding.FA_BF16, binding.FA_FP8_E4M3) for N in bench.SEQLENS
+             for c in (False, True)}
+    assert set(bench.MEASURED_TRAFFIC_BYTES_PER_LAUNCH) <= sweep
+
+
 def test_mfma_probe_validates_and_counts_flops():
     L = binding.lib()
     # 512 workgroups x 8 waves x iters x 32 MFMAs of 2*32*32*16 (bf16) or 2*32*32*64 (e4m3) FLOPs
@@ -94,15 +113,15 @@ def test_flop_accounting_matches_the_papers_ablation_table():
     import json
     g = json.load(open(os.path.join(ROOT, "tests", "golden", "paper_values.json")))
     row = g["ablation_full_method"]
-    fl = binding.attention_flops(row["batch"], row["nheads"], row["seqlen"], row["hdim"], row["causal"])
+    fl = bench.attention_flops(row["batch"], row["nheads"], row["seqlen"], row["hdim"], row["causal"])
     assert fl / (row["time_ms"] * 1e-3) / 1e12 == pytest.approx(row["tflops"], abs=0.6)
     for name in ("ablation_no_pipelining", "ablation_no_warp_specialization"):
         assert fl / (g[name]["time_ms"] * 1e-3) / 1e12 == pytest.approx(g[name]["tflops"], abs=0.6)
-    assert binding.attention_flops(1, 1, 8, 4, True) == 0.5 * binding.attention_flops(1, 1, 8, 4, False)
-    assert binding.attention_flops(1, 1, 8, 4, False, backward=True) == g["flops_rule"]["bwd_over_fwd"] * binding.attention_flops(1, 1, 8, 4, False)
+    assert bench.attention_flops(1, 1, 8, 4, True) == 0.5 * bench.attention_flops(1, 1, 8, 4, False)
+    assert bench.attention_flops(1, 1, 8, 4, False, backward=True) == g["flops_rule"]["bwd_over_fwd"] * bench.attention_flops(1, 1, 8, 4, False)
     # matmul FLOPs per exponential at head dim 128: 4*N^2*d / N^2 = 512
     e = g["exp_vs_matmul"]
-    assert binding.attention_flops(1, 1, 64, e["hdim"], False) / (64 * 64) == e["matmul_flops_per_exp"]
+    assert bench.attention_flops(1, 1, 64, e["hdim"], False) / (64 * 64) == e["matmul_flops_per_exp"]
 
 
 def test_mfma_hazard_checker_finds_planted_early_access():
