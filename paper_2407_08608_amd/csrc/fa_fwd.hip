@@ -15,6 +15,9 @@
 namespace fa {
 
 constexpr float kLazyLog2 = 8.0f;
+// fa_fwd_pingpong_kernel: a block whose per-lane sum of P~ exceeds this moves the row's reference (2^14:
+// every P~ of a block that stays below it fits fp16 with room to spare)
+constexpr float kRaiseAbove = 16384.0f;
 
 template <int D, int BC, int NT>
 struct TileCopy {
@@ -83,6 +86,8 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const uint16_t* vh = v + kv_off;
 
     const float sc = scale * kLog2e;  // exp(scale*s - scale*m) = exp2(sc*s - sc*m)
+    float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
+    asm volatile("" : "+v"(sc_v));
 
 #pragma nounroll
     for (int pass = 0; pass < n_pass; ++pass) {
@@ -91,26 +96,21 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     const int wave_q0 = qt * BR + wave * (32 * RQ);
 
     // Q_i^T as the B operand, resident in registers for the whole loop
-    i32x4 qreg[RQ][KS];
-#pragma unroll
-    for (int rq = 0; rq < RQ; ++rq) {
-        int row = min(wave_q0 + rq * 32 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
+    static_assert(RQ == 1 && PD == 0, "one 32-row slab per wave, operand reads scheduled by the compiler");
+    i32x4 qreg[KS];
+    {
+        int row = min(wave_q0 + col, N - 1);  // rows past N compute a copy of row N-1, never stored
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            qreg[rq][ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
+            qreg[ks] = *reinterpret_cast<const i32x4*>(qh + (size_t)row * D + ks * 16 + half * 8);
     }
 
-    f32x16 oacc[RQ][DT];
-    float m_run[RQ], l_run[RQ];
+    f32x16 oacc[DT];
+    float m_run = 0.f, l_run = 0.f;  // reference (log2 units of the scaled scores; set by block 0) and row sum of P~
 #pragma unroll
-    for (int rq = 0; rq < RQ; ++rq) {
-        m_run[rq] = -INFINITY;
-        l_run[rq] = 0.f;
+    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) oacc[rq][dt][r] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
 
     // key blocks this workgroup must visit
     int last_q = min(qt * BR + BR, N) - 1;
@@ -127,9 +127,7 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
     // entry, and the vmcnt waits it then needs at their first use sit inside the loop body,
     // where on every later iteration they would wait for the K/V prefetch just issued.
 #pragma unroll
-    for (int rq = 0; rq < RQ; ++rq)
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[rq][ks]));
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qreg[ks]));
     __syncthreads();
 
     // transposing V read: lane -> (row within a 4-key group, 4-column chunk) of its 16-lane group
@@ -148,51 +146,22 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
         // a wave whose queries all precede this block has nothing to add (causal)
         const bool wave_active = !CAUSAL || key0 <= wave_q0 + 32 * RQ - 1;
         if (wave_active) {
-            // ---- GEMM0: S^T = K_j Q_i^T
-            f32x16 sacc[RQ][KT];
-            const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
-            if constexpr (PD > 0) {
-                // Operand reads run PD MFMA steps ahead of their use, and the scheduler may move only
-                // VALU / SALU work across a step: with one wave per SIMD nothing else hides LDS latency.
-                constexpr int NU = KS * KT;
-                constexpr int P0 = PD < NU ? PD : NU;
-                i32x4 abuf[P0];
+            // ---- GEMM0: S^T = K_j Q_i^T, then the mask: keys past N, and keys after the query when causal
+            f32x16 sacc[KT];
+            const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
+            auto scores = [&]() __attribute__((always_inline)) {
+                const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const uint16_t* ks_base = lds_k[st] + col * KSTR + half * 8;
 #pragma unroll
-                for (int u = 0; u < P0; ++u)
-                    abuf[u] = *reinterpret_cast<const i32x4*>(ks_base + (u % KT) * 32 * KSTR + (u / KT) * 16);
-#pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    const int ks = u / KT, kt = u % KT;
-                    i32x4 a = abuf[u % P0];
-                    if (u + P0 < NU)
-                        abuf[u % P0] = *reinterpret_cast<const i32x4*>(ks_base + ((u + P0) % KT) * 32 * KSTR +
-                                                                       ((u + P0) / KT) * 16);
-#pragma unroll
-                    for (int rq = 0; rq < RQ; ++rq)
-                        sacc[rq][kt] = E::mma(a, qreg[rq][ks], ks == 0 ? zero : sacc[rq][kt]);
-                    __builtin_amdgcn_sched_barrier(0x6);
-                }
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
+                for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                     for (int kt = 0; kt < KT; ++kt) {
                         i32x4 a = *reinterpret_cast<const i32x4*>(ks_base + kt * 32 * KSTR + ks * 16);
-#pragma unroll
-                        for (int rq = 0; rq < RQ; ++rq)
-                            sacc[rq][kt] = E::mma(a, qreg[rq][ks], ks == 0 ? zero : sacc[rq][kt]);
+                        sacc[kt] = E::mma(a, qreg[ks], ks == 0 ? zero : sacc[kt]);
                     }
-                }
-            }
-
-            // ---- mask: keys past N, and keys after the query when causal
-            const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
-            if (need_mask) {
-#pragma unroll
-                for (int rq = 0; rq < RQ; ++rq) {
-                    int qi = wave_q0 + rq * 32 + col;
-                    int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+                if (need_mask) {
+                    const int qi = wave_q0 + col;
+                    const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
                     // compile-time key offsets against one opaque per-lane bound: a compare and a select per
                     // score, no index arithmetic
                     int bound = limit - key0 - 4 * half;
@@ -201,93 +170,83 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
                     for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
                         for (int r = 0; r < 16; ++r)
-                            if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) sacc[rq][kt][r] = -INFINITY;
+                            if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) sacc[kt][r] = -INFINITY;
                 }
-            }
-
-            // ---- online softmax (Algorithm 1: m, P~, l) and the operand for GEMM1
-            i32x4 pb[RQ][SL];
-#pragma unroll
-            for (int rq = 0; rq < RQ; ++rq) {
-                float mx = sacc[rq][0][0];
+            };
+            // The row's reference m (log2 units of the scaled scores) becomes the maximum of the block in
+            // `sacc` for the lanes that ask for it; O and l follow.
+            auto move_reference = [&](bool wanted, auto first_block) __attribute__((always_inline)) {
+                float mxp[4] = {sacc[0][0], sacc[0][1], sacc[0][2], sacc[0][3]};
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sacc[rq][kt][r]);
-                mx = max_both_halves(mx);
-                // The reference maximum is raised only when the block's maximum exceeds it by more
-                // than 2^kLazyLog2 in the exponent: P~ <= 2^kLazyLog2 otherwise, the factor cancels
-                // in O / l, and the O rescale (the costliest VALU step) is skipped on most blocks.
-                const bool raise = (mx - m_run[rq]) * sc > kLazyLog2;
-                if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-                    float corr = raise ? fast_exp2((m_run[rq] - mx) * sc) : 1.0f;
-                    m_run[rq] = raise ? mx : m_run[rq];
-                    l_run[rq] *= corr;
+                    for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
+                const float m_new = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]))) * sc;
+                if constexpr (decltype(first_block)::value) {  // O and l are still zero: only m changes
+                    m_run = m_new;
+                } else {
+                    const float corr = wanted ? fast_exp2(m_run - m_new) : 1.0f;
+                    m_run = wanted ? m_new : m_run;
+                    l_run *= corr;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                        for (int r = 0; r < 16; ++r) oacc[rq][dt][r] *= corr;
+                        for (int r = 0; r < 16; ++r) oacc[dt][r] *= corr;
                 }
-                float mb = m_run[rq] * sc;
-                float psum = 0.f;
+            };
+            // P~ = exp2(s c - m) packed as the operand for GEMM1; returns this lane's part of the row sum
+            i32x4 pb[SL];
+            auto probabilities = [&]() __attribute__((always_inline)) {
+                float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int kt = 0; kt < KT; ++kt) {
                     float p[16];
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
-                        p[r] = fast_exp2(__builtin_fmaf(sacc[rq][kt][r], sc, -mb));
-                        psum += p[r];
+                        p[r] = fast_exp2(__builtin_fmaf(sacc[kt][r], sc_v, -m_run));
+                        ps[r & 3] += p[r];
                     }
 #pragma unroll
                     for (int s2 = 0; s2 < 2; ++s2) {
                         i32x4 w;
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) w[e] = E::pack2(p[8 * s2 + 2 * e], p[8 * s2 + 2 * e + 1]);
-                        pb[rq][2 * kt + s2] = w;
+                        for (int i = 0; i < 4; ++i) w[i] = E::pack2(p[8 * s2 + 2 * i], p[8 * s2 + 2 * i + 1]);
+                        pb[2 * kt + s2] = w;
                     }
                 }
-                l_run[rq] += psum;
+                return (ps[0] + ps[1]) + (ps[2] + ps[3]);
+            };
+
+            // ---- online softmax (Algorithm 1: m, P~, l) without a row maximum per block.  The reference m
+            // is block 0's true row maximum and afterwards moves only when a block's row sum of P~ --
+            // computed anyway -- exceeds kRaiseAbove: below that every P~ of the block is below it too (also
+            // as a 16-bit value of the fp16 path), the reference cancels in O / l, and L = m + log2 l
+            // either way.  A block that does exceed it (scores that rose by more than 14 in log2 units
+            // since the reference was set: rare) is computed again from the K tile, which is still in
+            // LDS, with its own maximum as the new reference.
+            scores();
+            if (t == 0) move_reference(true, std::true_type{});
+            float blk = probabilities();
+            const bool over = max_both_halves(blk) > kRaiseAbove;
+            if (__builtin_amdgcn_ballot_w64(over) != 0) {
+                scores();
+                move_reference(over, std::false_type{});
+                blk = probabilities();
             }
+            l_run += blk;
 
             // ---- GEMM1: O^T += V_j^T P^T
             const uint16_t* vs_base = lds_v[st] + (4 * half + tr_row) * VSTR + tr_col;
-            if constexpr (PD > 0) {
-                constexpr int NU = SL * DT;
-                constexpr int P0 = PD < NU ? PD : NU;
-                i32x2 lo[P0], hi[P0];
 #pragma unroll
-                for (int u = 0; u < P0; ++u) {
-                    const uint16_t* p0 = vs_base + ((u / DT) * 16) * VSTR + (u % DT) * 32;
-                    lo[u] = lds_read_tr16(p0);
-                    hi[u] = lds_read_tr16(p0 + 8 * VSTR);
+            for (int sl = 0; sl < SL; ++sl)
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
+                    i32x2 lo = lds_read_tr16(p0);
+                    i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
+                    i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
+                    oacc[dt] = E::mma(a, pb[sl], oacc[dt]);
                 }
-#pragma unroll
-                for (int u = 0; u < NU; ++u) {
-                    const int sl = u / DT, dt = u % DT;
-                    i32x4 a = {lo[u % P0][0], lo[u % P0][1], hi[u % P0][0], hi[u % P0][1]};
-                    if (u + P0 < NU) {
-                        const uint16_t* p0 = vs_base + (((u + P0) / DT) * 16) * VSTR + ((u + P0) % DT) * 32;
-                        lo[u % P0] = lds_read_tr16(p0);
-                        hi[u % P0] = lds_read_tr16(p0 + 8 * VSTR);
-                    }
-#pragma unroll
-                    for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
-                    __builtin_amdgcn_sched_barrier(0x6);
-                }
-            } else {
-#pragma unroll
-                for (int sl = 0; sl < SL; ++sl) {
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        const uint16_t* p0 = vs_base + (sl * 16) * VSTR + dt * 32;
-                        i32x2 lo = lds_read_tr16(p0);
-                        i32x2 hi = lds_read_tr16(p0 + 8 * VSTR);
-                        i32x4 a = {lo[0], lo[1], hi[0], hi[1]};
-#pragma unroll
-                        for (int rq = 0; rq < RQ; ++rq) oacc[rq][dt] = E::mma(a, pb[rq][sl], oacc[rq][dt]);
-                    }
-                }
-            }
         }
 
         if (more) {
@@ -299,16 +258,15 @@ fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__
 
     // ---- epilogue: O / l, L = m + log l.  Every LDS read of the loop was followed by a barrier,
     // so the K and V buffers are free: each wave takes 4 KiB of them to transpose its output tile.
-    static_assert(RQ == 1, "one 32-row slab per wave");
     {
         char* patch = (wave < 4 ? reinterpret_cast<char*>(&lds_k[0][0]) : reinterpret_cast<char*>(&lds_v[0][0])) +
                       (wave & 3) * 4096;
         static_assert(sizeof(lds_k) >= 4 * 4096 && sizeof(lds_v) >= 4 * 4096, "patches must fit");
         const int qi = wave_q0 + col;
-        const float l = sum_both_halves(l_run[0]);
-        store_rows_via_lds<Tag, DT>(oacc[0], 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2), wave_q0,
+        const float l = sum_both_halves(l_run);
+        store_rows_via_lds<Tag, DT>(oacc, 1.0f / l, patch, make_buffer(o + head_off, (uint32_t)N * D * 2), wave_q0,
                                     lane);
-        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run[0] * sc + log2f(l)) * kLn2;
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l)) * kLn2;
     }
     if (pass + 1 < n_pass) __syncthreads();  // the next pass's first tile overwrites the patches
     }  // passes of a causal pair
@@ -665,7 +623,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
 
     i32x4 qreg[KS];
     f32x16 oacc[DT];
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = 0.f, l_run = 0.f;  // reference (log2 units of the scaled scores) and row sum of P~
 
     // ---- staging: wave w loads rows 4w .. 4w+3 and 32+4w .. 32+4w+3 of a tile (1 KiB each)
     const size_t kv_off = (size_t)(bh / kv_group) * N * D;  // grouped-query: kv_group query heads per K/V head
@@ -751,62 +709,81 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
         if ((key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0)) {
             const int qi = wave_q0 + col;
             const int limit = CAUSAL ? min(qi, N - 1) : N - 1;  // last visible key
+            // compile-time key offsets against one opaque per-lane bound: a compare and a select per score
+            int bound = limit - key0 - 4 * half;
+            asm volatile("" : "+v"(bound));
 #pragma unroll
             for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    int key = key0 + kt * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (key > limit) sacc[kt][r] = -INFINITY;
-                }
+                for (int r = 0; r < 16; ++r)
+                    if (kt * 32 + 8 * (r >> 2) + (r & 3) > bound) sacc[kt][r] = -INFINITY;
         }
         // Every step below is a batch of independent instructions: a wave gets few issue slots
-        // while its SIMD sibling streams MFMAs, and dependent chains (max, fma -> exp, sum)
-        // would turn each slot missed into a stall.
-        float mxp[4];
-#pragma unroll
-        for (int c = 0; c < 4; ++c) mxp[c] = sacc[0][c];
-#pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
-        float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])));
-        // lazily raised reference maximum, as in fa_fwd_16bit_kernel
-        const bool raise = (mx - m_run) * sc > kLazyLog2;
-        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-            float corr = raise ? fast_exp2((m_run - mx) * sc) : 1.0f;
-            m_run = raise ? mx : m_run;
-            l_run *= corr;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) oacc[dt][r] *= corr;
-        }
-        const float mb = m_run * sc;
-        __builtin_amdgcn_sched_barrier(0);
+        // while its SIMD sibling streams MFMAs, and dependent chains (fma -> exp, sum) would turn
+        // each slot missed into a stall.
+        //
+        // No row maximum is taken per block.  Scores are referred to a per-row reference m (log2
+        // units) that is the true row maximum of block 0 and afterwards moves only when a block's
+        // P~ grow large: x = s c - m stays in the score registers, P~ = exp2(x) goes to the operand
+        // registers, and the block's row sum -- needed anyway -- is the overflow detector.  While it
+        // stays below kRaiseAbove every P~ of the block is below it too (also the 16-bit P~ of the
+        // fp16 path); otherwise the reference is moved to this block's true maximum, O and l are
+        // rescaled and the block's P~ recomputed from x.  The reference cancels in O / l and L is
+        // m + log2 l either way, so the result is that of Algorithm 1 with any reference.
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kt][r] = __builtin_fmaf(sacc[kt][r], sc_v, -mb);
+            for (int r = 0; r < 16; ++r) sacc[kt][r] = __builtin_fmaf(sacc[kt][r], sc_v, -m_run);
         __builtin_amdgcn_sched_barrier(0);
+        float blk = 0.f;
+        auto probabilities = [&]() __attribute__((always_inline)) {
+            float ps[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt)
+            for (int kt = 0; kt < KT; ++kt) {
+                float e[16];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) sacc[kt][r] = fast_exp2(sacc[kt][r]);
-        __builtin_amdgcn_sched_barrier(0);
-        float ps[4] = {0.f, 0.f, 0.f, 0.f};
+                for (int r = 0; r < 16; ++r) e[r] = fast_exp2(sacc[kt][r]);
 #pragma unroll
-        for (int kt = 0; kt < KT; ++kt) {
+                for (int r = 0; r < 16; ++r) ps[r & 3] += e[r];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) ps[r & 3] += sacc[kt][r];
+                for (int s2 = 0; s2 < 2; ++s2) {
+                    i32x4 w;
 #pragma unroll
-            for (int s2 = 0; s2 < 2; ++s2) {
-                i32x4 w;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) w[e] = E::pack2(sacc[kt][8 * s2 + 2 * e], sacc[kt][8 * s2 + 2 * e + 1]);
-                pb[2 * kt + s2] = w;
+                    for (int i = 0; i < 4; ++i) w[i] = E::pack2(e[8 * s2 + 2 * i], e[8 * s2 + 2 * i + 1]);
+                    pb[2 * kt + s2] = w;
+                }
             }
+            blk = (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        };
+        probabilities();
+        const bool first = t == 0;
+        const bool raise = first || max_both_halves(blk) > kRaiseAbove;
+        if (first || __builtin_amdgcn_ballot_w64(raise) != 0) {
+            float mxp[4];
+#pragma unroll
+            for (int c = 0; c < 4; ++c) mxp[c] = sacc[0][c];
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mxp[r & 3] = fmaxf(mxp[r & 3], sacc[kt][r]);
+            const float mx = max_both_halves(fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3])));
+            const float delta = raise ? mx : 0.f;
+            const float corr = fast_exp2(-delta);
+            m_run += delta;
+            l_run *= corr;
+            if (!first) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) oacc[dt][r] *= corr;
+            }
+#pragma unroll
+            for (int kt = 0; kt < KT; ++kt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) sacc[kt][r] -= delta;
+            probabilities();
         }
-        l_run += (ps[0] + ps[1]) + (ps[2] + ps[3]);
+        l_run += blk;
         // P~ must exist in registers here: the compiler is otherwise free to sink the exponentials
         // past the next barrier, next to the MFMAs that consume them
 #pragma unroll
@@ -847,7 +824,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
-    m_run = -INFINITY;
+    m_run = 0.f;  // set from block 0's row maximum by its softmax
     l_run = 0.f;
     const int last_q = min(qt * BR + BR, N) - 1;
     const int n_blocks = CAUSAL ? (last_q / BC + 1) : ((N + BC - 1) / BC);
@@ -906,7 +883,7 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
         const float l = sum_both_halves(l_run);
         store_rows_via_lds<Tag, DT>(oacc, 1.0f / l, lds_o + wave * 4096, make_buffer(o + head_off, (uint32_t)N * D * 2),
                                     wave_q0, lane);
-        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run * sc + log2f(l)) * kLn2;
+        if (qi < N && half == 0) lse[(size_t)bh * N + qi] = (m_run + log2f(l)) * kLn2;
     }
     }  // passes of a causal pair
 }
