@@ -19,6 +19,26 @@
 #include "fa_device.h"
 #include "fa_launch.h"
 
+// Measurement builds only (paper_2407_08608_amd/ablate.py compiles this file with them; the library never
+// defines them).  FA_ABLATE removes one part of fa_fwd_fp8_kernel's block to see what the rest costs -- the
+// results are wrong on purpose: 1 = no exponentials, 2 = no LDS reads for the second GEMM, 3 = no second GEMM,
+// 4 = no softmax arithmetic (scale, exponential, row sum).  FA_PHASE_TRACE stamps the phases of 32 blocks
+// of one workgroup of the eight-wave d = 128 instantiation with the shader clock.
+#ifndef FA_ABLATE
+#define FA_ABLATE 0
+#endif
+#ifdef FA_PHASE_TRACE
+__device__ long long fa_phase_trace[8][32][8];
+extern "C" int fa_debug_read_phase_trace(void* host) {
+    return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(fa_phase_trace), sizeof(fa_phase_trace));
+}
+#define FA_STAMP(i) do { if (tracing) stamps[i] = __builtin_readcyclecounter(); } while (0)
+#define FA_STAMP_AFTER(i, ...) do { if (tracing) { asm volatile("s_nop 0" : __VA_ARGS__); stamps[i] = __builtin_readcyclecounter(); } } while (0)
+#else
+#define FA_STAMP(i) do { } while (0)
+#define FA_STAMP_AFTER(i, ...) do { } while (0)
+#endif
+
 namespace fa {
 
 constexpr float kPBias = 6.0f;
@@ -143,6 +163,11 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
         const int st = t & 1;
         const int key0 = t * BC;
         const bool more = (t + 1 < n_blocks);
+#ifdef FA_PHASE_TRACE
+        const bool tracing = D == 128 && NW == 8 && !CAUSAL && blockIdx.x == 300 && t >= 60 && t < 92;
+        long long stamps[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+        FA_STAMP(0);
         if (more) {
             load_tile(k_rsrc, key0 + BC, kpre);
             load_tile(v_rsrc, key0 + BC, vpre);
@@ -170,6 +195,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                     sacc[kt] = mma_fp8(a, qreg[ks], ks == 0 ? zero : sacc[kt]);
                 }
 
+            FA_STAMP_AFTER(1, "+v"(sacc[0]), "+v"(sacc[KT - 1]));  // scores done
             const bool need_mask = (key0 + BC > N) || (CAUSAL && key0 + BC - 1 > wave_q0);
             if (need_mask) {
                 int qi = wave_q0 + col;
@@ -211,6 +237,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 #pragma unroll
                     for (int r = 0; r < 16; ++r) oacc[dt][r] *= f;
             }
+            FA_STAMP(2);  // mask, row maximum, reference
             const float mb = m_run - kPBias - lsv;
             float sc_v = sc;  // a vector-register copy: an FMA with a scalar-register operand issues at a lower rate
             asm volatile("" : "+v"(sc_v));
@@ -221,8 +248,16 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                 float p[16];
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
+#if FA_ABLATE == 1
+                    p[r] = __builtin_fmaf(sacc[kt][r], sc_v, -mb);
+#elif FA_ABLATE == 4
+                    p[r] = sacc[kt][r];
+#else
                     p[r] = fast_exp2(__builtin_fmaf(sacc[kt][r], sc_v, -mb));
+#endif
+#if FA_ABLATE != 4
                     ps[r & 3] += p[r];
+#endif
                 }
 #pragma unroll
                 for (int w = 0; w < 4; ++w) {
@@ -236,6 +271,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
             if constexpr (SCALED) psum *= __builtin_amdgcn_rcpf(sv_new);
             l_run += psum;
 
+            FA_STAMP_AFTER(3, "+v"(pb[0]), "+v"(l_run));  // P~ done
             // ---- GEMM1: O^T += V_j^T P^T
             const uint8_t* vs_base = lds_v[st] + (8 * half + tr_row) * VSTR + tr_col;
 #pragma unroll
@@ -243,20 +279,36 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
                     i32x8 a;
+#if FA_ABLATE == 2
+                    a = qreg[0];
+                    asm volatile("" : "+v"(a));
+#else
 #pragma unroll
                     for (int u = 0; u < 4; ++u) {
                         i32x2 w = lds_read_tr8(vs_base + (sl * 64 + 16 * u) * VSTR + dt * 32);
                         a[2 * u] = w[0];
                         a[2 * u + 1] = w[1];
                     }
+#endif
+#if FA_ABLATE == 3
+                    asm volatile("" ::"v"(a), "v"(pb[sl]));
+#else
                     oacc[dt] = mma_fp8(a, pb[sl], oacc[dt]);
+#endif
                 }
         }
+        FA_STAMP_AFTER(4, "+v"(oacc[0]), "+v"(oacc[DT - 1]));  // products done
         if (more) {
             store_tile(lds_k[st ^ 1], KSTR, kpre);
             store_tile(lds_v[st ^ 1], VSTR, vpre);
         }
+        FA_STAMP(5);  // next tiles written to LDS
         __syncthreads();
+        FA_STAMP(6);  // barrier passed
+#ifdef FA_PHASE_TRACE
+        if (tracing && lane == 0)
+            for (int i = 0; i < 7; ++i) fa_phase_trace[wave][t - 60][i] = stamps[i];
+#endif
     }
 
     // ---- epilogue: O * s_V / l as bf16 (transposed through a wave-private LDS patch), L
