@@ -83,6 +83,10 @@ def main():
                     help="for rocprofv3 --pmc runs: three launches of the bf16 backward (bwd) or of the block-scaled "
                          "FP8 forward (fp8) at seqlen 16k, d = 128, non-causal, or of one forced schedule of the "
                          "fp16 forward at the ablation shape (batch 4, seqlen 8448); prints nothing")
+    ap.add_argument("--short-seq-probe", action="store_true",
+                    help="instead of the benchmark: seqlen 512 and 1024 at head dimension 128 over a range of batch "
+                         "sizes and tile shapes (how the launch time splits into a fixed part and a part per round "
+                         "of workgroups); prints one JSON line")
     ap.add_argument("--mfma-probe", action="store_true",
                     help="instead of the benchmark: the MFMA-only rate of the chip (bf16 and e4m3) on constant and "
                          "on random operand bits; prints one JSON line")
@@ -103,6 +107,9 @@ def main():
         return
     if args.counter_probe:
         counter_probe(torch, binding, inputs, dev, args.counter_probe)
+        return
+    if args.short_seq_probe:
+        print(json.dumps(short_seq_probe(torch, binding, inputs, dev)))
         return
     d = HEAD_DIM
     scale = d ** -0.5
@@ -282,6 +289,34 @@ def mfma_probe(torch, binding, inputs, dev):
         ms = _time_call(torch, lambda: binding.fa_probe_mfma(t, code, iters), reps=8, warm=4)
         out[f"{name}_{kind}"] = round(binding.fa_probe_mfma_flops(code, iters) / ms / 1e9, 1)
     return out
+
+
+def short_seq_probe(torch, binding, inputs, dev):
+    """Short sequences (bf16, 16 heads, d = 128): launch time against the number of workgroups per CU.
+    One row per (seqlen, mask, batch): the library's own choice of kernel and, for comparison, the three
+    forced schedules.  256 CUs; a 128-row tile launch has batch * 16 * seqlen / 128 workgroups (causal:
+    half, tiles are paired), two of which fit a CU at a time."""
+    d, H, rows = 128, 16, {}
+    scheds = (("auto", binding.FA_SCHED_AUTO), ("lockstep_4w", binding.FA_SCHED_LOCKSTEP_4W),
+              ("lockstep_8w", binding.FA_SCHED_LOCKSTEP_8W), ("pingpong", binding.FA_SCHED_PINGPONG))
+    for N in (512, 1024):
+        for B in (4, 8, 16, 32, 64, 128):
+            q, k, v = (t.to(dev) for t in inputs.qkv(4000 + N + B, B, H, N, d, "bf16"))
+            o = torch.empty_like(q)
+            lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+            for causal in (False, True):
+                row = {}
+                for name, sched in scheds:
+                    ms = min(_time_call(torch, lambda: binding.fa_fwd_schedule(q, k, v, d ** -0.5, causal, sched,
+                                                                               o=o, lse=lse), reps=20, warm=3)
+                             for _ in range(2))
+                    row[name] = {"us": round(ms * 1e3, 1),
+                                 "tflops": round(attention_flops(B, H, N, d, causal) / ms / 1e9, 1),
+                                 "hbm_frac": round(_hbm_bytes(B, H, N, d, False) / (ms * 1e-3) / PEAK_HBM_BYTES_PER_S, 3)}
+                tiles = B * H * N // 128
+                row["workgroups_of_128_rows_per_cu"] = round((tiles // 2 if causal else tiles) / 256, 2)
+                rows[f"N{N}_B{B}_{'causal' if causal else 'full'}"] = row
+    return rows
 
 
 def counter_probe(torch, binding, inputs, dev, which):
