@@ -19,8 +19,11 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous with respect to the host: they enqueue kernels and return.  They
  *     never synchronise, allocate or free device memory, throw, or abort.
- *   - The return value is an fa_status.  On any status other than FA_OK nothing has
- *     been launched by that call.  fa_status_string() names a status.
+ *   - The return value is an fa_status.  Every argument and size check precedes the first
+ *     launch: on any status other than FA_OK and FA_ERR_LAUNCH nothing has been enqueued.
+ *     FA_ERR_LAUNCH means the HIP runtime refused a launch; calls made of several kernels
+ *     (fa_bwd*: three, fa_fp8_quant_hadamard with per_tensor = 1: four) stop at the refused
+ *     one, and the outputs are then undefined.  fa_status_string() names a status.
  *   - Supported head dimensions: d in {64, 128, 256}.  N >= 1 (any N; rows past N are
  *     never read or written).  B, H >= 1.  scale finite and > 0.  causal in {0, 1};
  *     causal means key j is visible to query i iff j <= i (N_q == N_k).
@@ -75,7 +78,11 @@ int fa_fwd(const void* q, const void* k, const void* v, void* o, float* lse,
  * and K-block scales at no extra cost).
  *   q8, k8, v8 : e4m3 codes [B,H,N,d]                         (device, read)
  *   q_scale, k_scale, v_scale : fp32 [B,H,ceil(N/block_rows)]; the real tensor is
- *             code * scale of its block                        (device, read)
+ *             code * scale of its block                        (device, read).  Every scale must
+ *             be finite and > 0 (an all-zero block carries scale 1, as fa_fp8_quant_hadamard
+ *             writes it): log2(v_scale) and 1 / v_scale enter the row maximum and the row sum,
+ *             so a zero, negative or non-finite scale gives NaN rows.  Not checked (the values
+ *             live on the device).
  *   o   : bf16 [B,H,N,d]; lse : fp32 [B,H,N]                   (device, written)
  *   block_rows : rows per quantisation block; must be 128.
  * Q and K are expected to have been multiplied by the same orthogonal matrix

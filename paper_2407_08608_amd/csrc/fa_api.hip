@@ -35,6 +35,10 @@ void* noalloc_scratch_on_current_device() {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool head_dim_ok(int d) { return d == 64 || d == 128 || d == 256; }
 
+// A sticky error left on this thread by earlier, unrelated HIP work would otherwise be reported by the
+// first hipGetLastError() after our own launch and be mistaken for ours.
+void forget_stale_hip_error() { (void)hipGetLastError(); }
+
 int check_common(int B, int H, int N, int d, float scale, int causal) {
     if (B <= 0 || H <= 0 || N <= 0 || d <= 0) return FA_ERR_SHAPE;
     if (!(scale > 0.f) || !isfinite(scale)) return FA_ERR_SHAPE;
@@ -77,6 +81,7 @@ static int fwd_any(const void* q, const void* k, const void* v, void* o, float* 
     if (schedule != FA_SCHED_AUTO && dtype != FA_BF16 && dtype != FA_F16) return FA_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    forget_stale_hip_error();
     switch (dtype) {
         case FA_F32: return fa::launch_fwd_f32(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, s);
         case FA_BF16: return fa::launch_fwd_bf16(q, k, v, o, lse, B, H, H_kv, N, d, scale, causal, schedule, s);
@@ -95,6 +100,7 @@ static int fwd_fp8_any(const void* q8, const void* k8, const void* v8, const flo
     if (block_rows <= 0 || H_kv <= 0 || H % H_kv != 0) return FA_ERR_SHAPE;
     if (block_rows != 128) return FA_ERR_UNSUPPORTED;
     if (!aligned16(q8) || !aligned16(k8) || !aligned16(v8) || !aligned16(o) || !aligned16(lse)) return FA_ERR_ALIGN;
+    forget_stale_hip_error();
     return fa::launch_fwd_fp8(q8, k8, v8, q_scale, k_scale, v_scale, o, lse, B, H, H_kv, N, d, scale, causal,
                               static_cast<hipStream_t>(stream));
 }
@@ -148,6 +154,7 @@ int fa_fp8_quant_hadamard(const void* x, int in_dtype, void* x8, float* scales, 
     if ((long)B * H * N > 0x7fffffffL) return FA_ERR_SHAPE;
     if (!head_dim_ok(d) || block_rows != 128) return FA_ERR_UNSUPPORTED;
     if (!aligned16(x) || !aligned16(x8)) return FA_ERR_ALIGN;
+    forget_stale_hip_error();
     return fa::launch_quant_hadamard(x, in_dtype, x8, scales, B, H, N, d, signs, per_tensor,
                                      static_cast<hipStream_t>(stream));
 }
@@ -181,6 +188,7 @@ static int bwd_any(const void* q, const void* k, const void* v, const void* o, c
     if (st != FA_OK) return st;
     if (!workspace || workspace_bytes < fa::bwd_workspace_bytes(B, H, N, d)) return FA_ERR_WORKSPACE;
     if (!aligned16(workspace)) return FA_ERR_ALIGN;
+    forget_stale_hip_error();
     return fa::launch_bwd(q, k, v, o, lse, dout, dq, dk, dv, workspace, B, H, H_kv, N, d, scale, causal, dtype,
                           static_cast<hipStream_t>(stream));
 }
@@ -205,6 +213,7 @@ int fa_bwd_noalloc(const void* q, const void* k, const void* v, const void* o, c
     int st = check_bwd(q, k, v, o, lse, dout, dq, dk, dv, B, H, H, N, d, scale, causal, dtype);
     if (st != FA_OK) return st;
     if ((long)B * H * N > (long)FA_BWD_NOALLOC_MAX_ROWS) return FA_ERR_TOO_LARGE;
+    forget_stale_hip_error();
     void* scratch = noalloc_scratch_on_current_device();
     if (!scratch) return FA_ERR_LAUNCH;
     // D is written in full by the first kernel before the others read it: nothing to clear
@@ -224,6 +233,7 @@ int fa_probe_mfma(const void* operands, size_t operand_bytes, float* sink, int d
     if (operand_bytes < 16 || operand_bytes % 16 != 0 || operand_bytes > (size_t)1 << 30 || iters <= 0 || iters > 1000000)
         return FA_ERR_SHAPE;
     if (!aligned16(operands) || !aligned16(sink)) return FA_ERR_ALIGN;
+    forget_stale_hip_error();
     return fa::launch_probe_mfma(operands, operand_bytes, sink, iters, dtype == FA_FP8_E4M3,
                                  static_cast<hipStream_t>(stream));
 }

@@ -684,16 +684,21 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
     const long rows = (long)B * H * N;
     float* dvec = static_cast<float*>(workspace);
     auto u16 = [](const void* p) { return static_cast<const uint16_t*>(p); };
+    // every size check comes before the first launch: a call that fails has enqueued nothing
+    const int n_kblocks = (N + 127) / 128;
+    const long total = (long)B * H_kv * n_kblocks;
+    constexpr int BC = 64, NW = D == 256 ? 4 : 8;  // d = 256: a wave needs the whole register file
+    const int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
+    const long total_q = (long)B * H * n_qtiles;
+    if (total > 0x7fffffffL || total_q > 0x7fffffffL) return FA_ERR_SHAPE;
 
     constexpr int kRowsPerWg = 256 / (D / 8);
     hipLaunchKernelGGL((fa_bwd_preprocess_kernel<Tag, D>), dim3((unsigned)((rows + kRowsPerWg - 1) / kRowsPerWg)),
                        dim3(256), 0, stream,
                        u16(o), u16(dout), dvec, rows);
+    if (hipGetLastError() != hipSuccess) return FA_ERR_LAUNCH;
 
-    int n_kblocks = (N + 127) / 128;
-    long total = (long)B * H_kv * n_kblocks;
     const dim3 kv_grid((unsigned)total, D > 128 ? D / 128 : 1);  // y: 128-column slices of dK, dV
-    if (total > 0x7fffffffL) return FA_ERR_SHAPE;
     if (causal)
         hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, true>), kv_grid, dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
@@ -702,10 +707,8 @@ static int launch_bwd_t(const void* q, const void* k, const void* v, const void*
         hipLaunchKernelGGL((fa_bwd_dkdv_kernel<Tag, D, false>), kv_grid, dim3(256), 0, stream, u16(q),
                            u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dk),
                            static_cast<uint16_t*>(dv), N, n_kblocks, (int)total, H / H_kv, scale);
+    if (hipGetLastError() != hipSuccess) return FA_ERR_LAUNCH;
 
-    constexpr int BC = 64, NW = D == 256 ? 4 : 8;  // d = 256: a wave needs the whole register file
-    int n_qtiles = (N + NW * 32 - 1) / (NW * 32);
-    long total_q = (long)B * H * n_qtiles;
     if (causal)
         hipLaunchKernelGGL((fa_bwd_dq_kernel<Tag, D, BC, NW, true>), dim3((unsigned)total_q), dim3(NW * 64), 0, stream,
                            u16(q), u16(k), u16(v), u16(dout), lse, dvec, static_cast<uint16_t*>(dq), N, n_qtiles,

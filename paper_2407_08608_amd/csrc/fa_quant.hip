@@ -2,13 +2,15 @@
 // followed by block quantisation to e4m3 with one fp32 scale per 128 rows of a head.
 //
 // HBM-bound: every element is read once (2 or 4 bytes) and written once (1 byte).  One
-// workgroup owns one 128-row block; four lanes share a row, each holding d/4 elements as
-// 16-byte chunks interleaved across the four lanes so that global loads and stores are
-// coalesced.  The Hadamard butterflies run in the order of the element index bits
-// (strides 1, 2, ..., d/2): strides 1-4 inside a chunk, strides 8-16 across the four lanes
-// with DPP quad permutes, strides >= 32 across the lane's chunks.  All arithmetic that
-// decides a code is fp32: add/sub butterflies, one multiply by float(1/sqrt(d)), one
-// multiply by 448/amax, clamp, round-to-nearest-even conversion.
+// workgroup owns one 128-row block; d / 16 lanes (at least four) share a row, each holding its
+// part of the row as 8-element chunks interleaved across those lanes, so that global loads
+// (16 bytes per lane) and stores (8 bytes) are coalesced and a lane holds 32 values of the block
+// whatever the head dimension.  The Hadamard butterflies run in the order of the element index
+// bits (strides 1, 2, ..., d/2): strides 1-4 inside a chunk, strides 8-16 between neighbouring
+// lanes with DPP quad permutes, strides 32-64 (eight or sixteen lanes per row) with ds_swizzle lane
+// exchanges, the remaining strides across the lane's chunks.  All arithmetic that decides a code is
+// fp32: add/sub butterflies, one multiply by float(1/sqrt(d)), one multiply by 448/amax, clamp,
+// round-to-nearest-even conversion.
 #include "fa_device.h"
 #include "fa_launch.h"
 
@@ -224,10 +226,13 @@ static int launch_quant(const void* x, void* x8, float* scales, int B, int H, in
                            slot0, N, n_blocks);
     } else {
         hipLaunchKernelGGL(fa_zero_word_kernel, dim3(1), dim3(1), 0, stream, slot0);
+        if (hipGetLastError() != hipSuccess) return FA_ERR_LAUNCH;
         hipLaunchKernelGGL((fa_quant_kernel<D, IN_DTYPE, 1, HADAMARD>), grid, block, 0, stream, x, out, scales, signs,
                            slot0, N, n_blocks);
+        if (hipGetLastError() != hipSuccess) return FA_ERR_LAUNCH;
         hipLaunchKernelGGL((fa_quant_kernel<D, IN_DTYPE, 2, HADAMARD>), grid, block, 0, stream, x, out, scales, signs,
                            slot0, N, n_blocks);
+        if (hipGetLastError() != hipSuccess) return FA_ERR_LAUNCH;
         hipLaunchKernelGGL(fa_fill_scales_kernel, dim3(1), dim3(256), 0, stream, scales, total);
     }
     return hipGetLastError() == hipSuccess ? FA_OK : FA_ERR_LAUNCH;

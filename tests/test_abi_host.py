@@ -137,6 +137,13 @@ def test_mfma_hazard_checker_finds_planted_early_access():
     assert len(hz.check(head + "\tv_mov_b32_e32 v50, v31\n" + chain + wait + read)) == 1   # a copy between two MFMAs
     assert len(hz.check(head + "\tds_read_b128 v[28:31], v60\n" + wait)) == 1              # overwritten too early
     assert len(hz.check(head + "\ts_nop 7\n\tv_mfma_f32_32x32x16_bf16 a[0:15], v[16:19], v[8:11], a[0:15]\n")) == 1
+    # a reader at the head of a loop, reached only through the back-edge right behind the MFMA
+    loop = "_Z6kernelv:\n.LBB0_1:\n" + read + "\ts_nop 12\n\t;;#ASMSTART\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], a[0:3], 0\n\t;;#ASMEND\n"
+    assert len(hz.check(loop + "\ts_cbranch_scc1 .LBB0_1\n")) == 1
+    assert hz.check(loop + wait + "\ts_cbranch_scc1 .LBB0_1\n") == []
+    # a forward branch that skips the wait
+    skip = head + "\ts_cbranch_vccz .LBB0_2\n" + wait + ".LBB0_2:\n" + read
+    assert len(hz.check(skip)) == 1
     # an MFMA the compiler scheduled itself (no ASMSTART) is the compiler's business
     assert hz.check("_Z6kernelv:\n\tv_mfma_f32_32x32x16_bf16 v[16:31], v[0:3], v[4:7], 0\n" + read) == []
 
