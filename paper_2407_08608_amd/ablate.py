@@ -22,6 +22,9 @@ OUT = os.path.join(HERE, "csrc", "_build", "ablate")  # git-ignored, travels to 
 VARIANTS = {"full": [], "no_exponentials": ["-DFA_ABLATE=1"], "no_lds_reads_second_gemm": ["-DFA_ABLATE=2"],
             "no_second_gemm": ["-DFA_ABLATE=3"], "no_softmax_arithmetic": ["-DFA_ABLATE=4"],
             "phase_trace": ["-DFA_PHASE_TRACE"]}
+# the bf16 ping-pong kernel (fa_fwd.hip)
+VARIANTS_16 = {"full": [], "no_exponentials": ["-DFA_ABLATE_PP=1"], "no_v_operand_reads": ["-DFA_ABLATE_PP=2"],
+               "no_k_operand_reads": ["-DFA_ABLATE_PP=3"], "no_softmax_arithmetic": ["-DFA_ABLATE_PP=4"]}
 
 
 def build():
@@ -37,6 +40,15 @@ def build():
         subprocess.run([fa_build.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
                         os.path.join(OUT, f"libfa_{name}.so"), obj, *others], check=True)
         print("built", name, file=sys.stderr)
+    others = [os.path.join(fa_build.OBJ, f) for f in sorted(os.listdir(fa_build.OBJ))
+              if f.endswith(".hip.o") and f != "fa_fwd.hip.o"]
+    for name, flags in VARIANTS_16.items():
+        obj = os.path.join(OUT, f"fa_fwd_{name}.o")
+        subprocess.run([fa_build.HIPCC, *fa_build.FLAGS, *flags, "-c", os.path.join(fa_build.CSRC, "fa_fwd.hip"),
+                        "-o", obj], check=True, stderr=subprocess.DEVNULL)
+        subprocess.run([fa_build.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
+                        os.path.join(OUT, f"libfa16_{name}.so"), obj, *others], check=True)
+        print("built bf16", name, file=sys.stderr)
 
 
 def run(seqlens):
@@ -99,6 +111,48 @@ def run(seqlens):
         print(f"  wave {w}: period {np.diff(r[:, 0])[4:28].mean():6.0f}   " + "   ".join(f"{n} {x:5.0f}" for n, x in zip(names, seg)))
 
 
+def run16(seqlens):
+    """The bf16 forward at head dimension 128 (ping-pong kernel from 1024 keys on) with each variant."""
+    import torch
+    from . import inputs
+    d, dev = 128, torch.device("cuda:0")
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    libs = {}
+    for name in VARIANTS_16:
+        L = ctypes.CDLL(os.path.join(OUT, f"libfa16_{name}.so"))
+        L.fa_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, ci, vp]
+        L.fa_fwd.restype = ci
+        libs[name] = L
+    st = torch.cuda.current_stream().cuda_stream
+    for N in seqlens:
+        B, H = inputs.benchmark_shape(N, d)
+        q, k, v = (t.to(dev) for t in inputs.qkv(1000 + N, B, H, N, d, "bf16"))
+        o = torch.empty_like(q)
+        lse = torch.empty((B, H, N), device=dev, dtype=torch.float32)
+        flops = 4.0 * N * N * d * H * B
+        for causal in (0, 1):
+            row = []
+            for name, L in libs.items():
+                def call():
+                    r = L.fa_fwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), B, H, N, d,
+                                 d ** -0.5, causal, 1, st)
+                    assert r == 0
+                for _ in range(5):
+                    call()
+                torch.cuda.synchronize()
+                best = 1e9
+                for _ in range(2):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for _ in range(20):
+                        call()
+                    e1.record()
+                    torch.cuda.synchronize()
+                    best = min(best, e0.elapsed_time(e1) / 20)
+                row.append(f"{name} {flops * (0.5 if causal else 1) / best / 1e9:7.1f}")
+            print(f"bf16 N={N} causal={causal} nominal TFLOPs/s: " + "  ".join(row), flush=True)
+
+
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true")
@@ -108,4 +162,5 @@ if __name__ == "__main__":
     if a.build:
         build()
     if a.run:
+        run16([int(x) for x in a.seqlens.split(",")])
         run([int(x) for x in a.seqlens.split(",")])

@@ -12,6 +12,14 @@
 #include "fa_device.h"
 #include "fa_launch.h"
 
+// Measurement builds only (paper_2407_08608_amd/ablate.py compiles this file with it; the library never defines
+// it): FA_ABLATE_PP removes one part of fa_fwd_pingpong_kernel's block to see what the rest costs -- results
+// wrong on purpose: 1 = no exponentials, 2 = no LDS reads of V operands, 3 = no LDS reads of K operands,
+// 4 = no softmax arithmetic at all (P~ = packed scores).
+#ifndef FA_ABLATE_PP
+#define FA_ABLATE_PP 0
+#endif
+
 namespace fa {
 
 constexpr float kLazyLog2 = 8.0f;
@@ -668,14 +676,22 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
     auto read_unit = [&](auto do1, int t, int u) __attribute__((always_inline)) {
         constexpr int n1 = decltype(do1)::value ? N1 : 0;
         if (u < n1) {
+#if FA_ABLATE_PP == 2
+            asm volatile("" : "+v"(ring[u % P]));
+#else
             const int sl = u / DT, dt = u % DT;
             const char* p0 = lds_v + ((t - 1) & (NS - 1)) * TILE + vofs[dt] + sl * 16 * ROWB;
             i32x2 lo = lds_read_tr16(p0);
             i32x2 hi = lds_read_tr16(p0 + 8 * ROWB);
             ring[u % P] = i32x4{lo[0], lo[1], hi[0], hi[1]};
+#endif
         } else {
+#if FA_ABLATE_PP == 3
+            asm volatile("" : "+v"(ring[u % P]));
+#else
             const int ks = (u - n1) / KT, kt = (u - n1) % KT;
             ring[u % P] = *reinterpret_cast<const i32x4*>(lds_k + (t & (NS - 1)) * TILE + kofs[ks] + kt * 32 * ROWB);
+#endif
         }
     };
     auto prefill = [&](auto do1, auto do0, int t) __attribute__((always_inline)) {
@@ -730,10 +746,12 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
         // fp16 path); otherwise the reference is moved to this block's true maximum, O and l are
         // rescaled and the block's P~ recomputed from x.  The reference cancels in O / l and L is
         // m + log2 l either way, so the result is that of Algorithm 1 with any reference.
+#if FA_ABLATE_PP != 4
 #pragma unroll
         for (int kt = 0; kt < KT; ++kt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) sacc[kt][r] = __builtin_fmaf(sacc[kt][r], sc_v, -m_run);
+#endif
         __builtin_amdgcn_sched_barrier(0);
         float blk = 0.f;
         auto probabilities = [&]() __attribute__((always_inline)) {
@@ -742,9 +760,15 @@ fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restric
             for (int kt = 0; kt < KT; ++kt) {
                 float e[16];
 #pragma unroll
+#if FA_ABLATE_PP == 1 || FA_ABLATE_PP == 4
+                for (int r = 0; r < 16; ++r) e[r] = sacc[kt][r];
+#else
                 for (int r = 0; r < 16; ++r) e[r] = fast_exp2(sacc[kt][r]);
+#endif
+#if FA_ABLATE_PP != 4
 #pragma unroll
                 for (int r = 0; r < 16; ++r) ps[r & 3] += e[r];
+#endif
 #pragma unroll
                 for (int s2 = 0; s2 < 2; ++s2) {
                     i32x4 w;
