@@ -28,9 +28,10 @@ PEAK_HBM_BYTES_PER_S = 8.0e12  # published HBM3E bandwidth
 # by what the same counters read for a plain copy of known size), averaged over the launches of the sweep that
 # the named kernel serves.  Keyed by kernel name as the library reports it (fa_fwd_kernel_name): a kernel
 # that is renamed or re-tiled no longer matches and its traffic is reported as null until it is measured
-# again.  Sources: profiles/fa_fwd_bf16_d128_hbm_traffic.txt, profiles/fa_fwd_fp8_d128_hbm_traffic.txt.
+# again.  Source: profiles/fa_fwd_d128_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
     "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>": 2.967e8,
+    "fa_fwd_fp8_kernel<128, 128, 8, false, true>": 1.909e8,
 }
 
 
