@@ -1,4 +1,4 @@
-"""Measurement aid: what each part of the FP8 forward's block costs on the GPU.
+"""Measurement aid: what each part of the forward's block costs on the GPU, and the clock the chip runs at.
 
 Builds variants of libfa_mi355.so in which fa_fwd_fp8.hip is compiled with FA_ABLATE=1..4 (one part of
 fa_fwd_fp8_kernel's block removed; results wrong on purpose) or with FA_PHASE_TRACE (shader-clock stamps at
@@ -7,6 +7,11 @@ FP8 forward at head dimension 128 with each of them on the seeded N(0,1) inputs 
 
     python -m paper_2407_08608_amd.ablate --build        # on the CPU (hipcc cross-compiles)
     python -m paper_2407_08608_amd.ablate --run          # on the GPU; prints a table
+    python -m paper_2407_08608_amd.ablate --clock        # on the GPU; shader-clock cycles and clock per kernel
+
+--clock uses one more library, every kernel file compiled with FA_CLOCK_SPAN (ClockSpan in fa_device.h): the
+main kernels record their first entry and last exit stamp on one CU, and cycles over wall time is the clock
+the chip granted that kernel.
 
 The library itself is never built with these switches.
 """
@@ -49,6 +54,15 @@ def build():
         subprocess.run([fa_build.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
                         os.path.join(OUT, f"libfa16_{name}.so"), obj, *others], check=True)
         print("built bf16", name, file=sys.stderr)
+    objs = []
+    for src in sorted(f for f in os.listdir(fa_build.CSRC) if f.endswith(".hip")):
+        obj = os.path.join(OUT, f"clock_span_{src}.o")
+        subprocess.run([fa_build.HIPCC, *fa_build.FLAGS, *fa_build.EXTRA_FLAGS.get(src, []), "-DFA_CLOCK_SPAN", "-c",
+                        os.path.join(fa_build.CSRC, src), "-o", obj], check=True, stderr=subprocess.DEVNULL)
+        objs.append(obj)
+    subprocess.run([fa_build.HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o",
+                    os.path.join(OUT, "libfa_clock_span.so"), *objs], check=True)
+    print("built clock_span", file=sys.stderr)
 
 
 def run(seqlens):
@@ -153,10 +167,79 @@ def run16(seqlens):
             print(f"bf16 N={N} causal={causal} nominal TFLOPs/s: " + "  ".join(row), flush=True)
 
 
+def clock(N):
+    """Cycles on one CU, wall time and the resulting clock of the main kernels at N keys (benchmark shapes)."""
+    import numpy as np
+    import torch
+    from . import binding, inputs
+    dev = torch.device("cuda:0")
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    L = ctypes.CDLL(os.path.join(OUT, "libfa_clock_span.so"))
+    L.fa_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, ci, vp]
+    L.fa_fwd_fp8.argtypes = [vp] * 8 + [ci] * 5 + [cf, ci, vp]
+    L.fa_bwd.argtypes = [vp] * 9 + [vp, ctypes.c_size_t] + [ci] * 4 + [cf, ci, ci, vp]
+    for f in (L.fa_fwd, L.fa_fwd_fp8, L.fa_bwd):
+        f.restype = ci
+    st = torch.cuda.current_stream().cuda_stream
+    reps = 5
+    print(f"{reps} launches back to back after 10 warm-up launches; cycles: first entry to last exit stamp on one CU")
+    for d in (128, 64, 256):
+        B, H = inputs.benchmark_shape(N, d)
+        q, k, v = (t.to(dev) for t in inputs.qkv(1000 + N, B, H, N, d, "bf16"))
+        do = inputs.qkv(2000 + N, B, H, N, d, "bf16")[0].to(dev)
+        signs = inputs.random_signs(1000, d).to(dev)
+        q8, qs = binding.fa_fp8_quant_hadamard(q, signs)
+        k8, ks = binding.fa_fp8_quant_hadamard(k, signs)
+        v8, vs = binding.fa_fp8_quant_hadamard(v, None)
+        o, lse = binding.fa_fwd(q, k, v, d ** -0.5, False)
+        o8 = torch.empty_like(q)
+        dq, dk, dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        ws = torch.empty(B * H * N, device=dev, dtype=torch.float32)
+        for causal in (0, 1):
+            if causal:
+                o, lse = binding.fa_fwd(q, k, v, d ** -0.5, True)
+            calls = {
+                "fwd bf16": (L.fa_debug_clock_span_fwd, 4.0, lambda: L.fa_fwd(
+                    q.data_ptr(), k.data_ptr(), v.data_ptr(), o8.data_ptr(), lse.data_ptr(), B, H, N, d, d ** -0.5,
+                    causal, binding.FA_BF16, st)),
+                "fwd fp8": (L.fa_debug_clock_span_fwd_fp8, 4.0, lambda: L.fa_fwd_fp8(
+                    q8.data_ptr(), k8.data_ptr(), v8.data_ptr(), qs.data_ptr(), ks.data_ptr(), vs.data_ptr(),
+                    o8.data_ptr(), lse.data_ptr(), B, H, N, d, 128, d ** -0.5, causal, st)),
+                "bwd bf16": (L.fa_debug_clock_span_bwd, 10.0, lambda: L.fa_bwd(
+                    q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), do.data_ptr(),
+                    dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), ws.data_ptr(), ws.numel() * 4, B, H, N, d,
+                    d ** -0.5, causal, binding.FA_BF16, st)),
+            }
+            for what, (reader, flop_factor, call) in calls.items():
+                if what == "fwd fp8":
+                    lse_keep = lse.clone()  # the FP8 forward overwrites L, which the backward reads
+                span = np.zeros(2, dtype=np.uint64)
+                reader.argtypes = [vp]
+                for _ in range(10):
+                    assert call() == 0
+                assert reader(span.ctypes.data_as(vp)) == 0
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    assert call() == 0
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1)
+                assert reader(span.ctypes.data_as(vp)) == 0
+                cycles = int(span[1]) - int(span[0])
+                flops = flop_factor * N * N * d * H * B * (0.5 if causal else 1) * reps
+                print(f"d={d:3d} N={N} causal={causal} {what}: {ms / reps:7.4f} ms per launch  {flops / ms / 1e9:7.1f} "
+                      f"nominal TFLOPs/s  {cycles / reps:10.0f} cycles per launch  clock {cycles / ms / 1e6:5.3f} GHz",
+                      flush=True)
+                if what == "fwd fp8":
+                    lse.copy_(lse_keep)
+
+
 if __name__ == "__main__":
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true")
     ap.add_argument("--run", action="store_true")
+    ap.add_argument("--clock", action="store_true")
     ap.add_argument("--seqlens", default="4096,16384")
     a = ap.parse_args()
     if a.build:
@@ -164,3 +247,5 @@ if __name__ == "__main__":
     if a.run:
         run16([int(x) for x in a.seqlens.split(",")])
         run([int(x) for x in a.seqlens.split(",")])
+    if a.clock:
+        clock(int(a.seqlens.split(",")[-1]))

@@ -262,4 +262,44 @@ static __device__ __forceinline__ int xcd_contiguous(int id, int total) {
     return (id % kXcd) * (total / kXcd) + id / kXcd;
 }
 
+// Measurement builds (-DFA_CLOCK_SPAN): how many shader-clock cycles a launch took on one CU.  A kernel
+// declares a ClockSpan as its first statement; workgroups that run on the chosen CU record the earliest
+// entry stamp and the latest exit stamp (the shader clock is only comparable within a CU).  The CU is that
+// of workgroup 0 of the first launch after the library is loaded, so that launch only chooses and the
+// launches after it measure.  Cycles divided by the launch's wall time is the clock the chip actually ran
+// at: it lowers the clock under load, so a kernel that needs fewer cycles need not take less time.  Each
+// source file that holds measured kernels defines its reader with FA_CLOCK_SPAN_READER(name).  In ordinary
+// builds ClockSpan is empty and generates no code.
+#ifdef FA_CLOCK_SPAN
+static __device__ unsigned long long fa_clock_span_cycles[2] = {~0ull, 0ull};
+static __device__ int fa_clock_span_cu = -1;
+struct ClockSpan {
+    long long t0;
+    __device__ __forceinline__ ClockSpan() : t0(__builtin_readcyclecounter()) {}
+    __device__ __forceinline__ ~ClockSpan() {
+        if (threadIdx.x == 0) {
+            // XCC id, then shader engine / shader array / CU from the hardware id register
+            const int cu = (int)(((__builtin_amdgcn_s_getreg((31 << 11) | 20) & 15) << 8) |
+                                 ((__builtin_amdgcn_s_getreg((31 << 11) | 4) >> 8) & 255));
+            if (blockIdx.x == 0 && fa_clock_span_cu < 0) fa_clock_span_cu = cu;
+            if (cu == fa_clock_span_cu) {
+                atomicMin(&fa_clock_span_cycles[0], (unsigned long long)t0);
+                atomicMax(&fa_clock_span_cycles[1], (unsigned long long)__builtin_readcyclecounter());
+            }
+        }
+    }
+};
+// span[0], span[1]: first entry and last exit stamp since the last call; the call clears them
+#define FA_CLOCK_SPAN_READER(name)                                                                              \
+    extern "C" int name(unsigned long long* span) {                                                             \
+        const unsigned long long init[2] = {~0ull, 0ull};                                                       \
+        if (hipDeviceSynchronize() != hipSuccess) return 1;                                                     \
+        if (hipMemcpyFromSymbol(span, HIP_SYMBOL(fa::fa_clock_span_cycles), sizeof(init)) != hipSuccess) return 2; \
+        return hipMemcpyToSymbol(HIP_SYMBOL(fa::fa_clock_span_cycles), init, sizeof(init)) == hipSuccess ? 0 : 3; \
+    }
+#else
+struct ClockSpan {};
+#define FA_CLOCK_SPAN_READER(name)
+#endif
+
 }  // namespace fa

@@ -61,6 +61,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                   const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                   const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
                   int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
+    ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
     constexpr int KSTR = D + 16;  // bytes per LDS row
@@ -340,6 +341,7 @@ fa_fwd_fp8_pipe_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict_
                        const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                        const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
                        int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
+    ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int BC = 64, NT = NW * 64, BR = NW * 32;
     // One wave per SIMD (d = 256, four waves): score MFMAs in inline assembly with explicit waits.  Two waves
     // per SIMD (d = 128, eight waves): at most 256 registers per lane, every MFMA result is in ordinary
@@ -761,3 +763,5 @@ const char* fwd_fp8_kernel_name(int N, int d, int causal) {
 }
 
 }  // namespace fa
+
+FA_CLOCK_SPAN_READER(fa_debug_clock_span_fwd_fp8)
