@@ -14,8 +14,11 @@ from paper_2407_08608_amd import binding, inputs
 pytestmark = pytest.mark.gpu
 
 
+@pytest.mark.parametrize("noalloc", [False, True])
 @pytest.mark.parametrize("causal", [False, True])
-def test_forward_backward_graph_replays_match_eager(causal):
+def test_forward_backward_graph_replays_match_eager(causal, noalloc):
+    # noalloc: the backward on the library's own scratch (the entry point meant for callers under capture); its
+    # scratch address is resolved by the eager calls below, before the capture begins
     B, H, N, d = 2, 4, 1300, 128
     scale = d ** -0.5
     sets = [tuple(t.cuda() for t in (*inputs.qkv(200 + i, B, H, N, d, "bf16"),
@@ -28,7 +31,10 @@ def test_forward_backward_graph_replays_match_eager(causal):
 
     def step():
         binding.fa_fwd(q, k, v, scale, causal, o=o, lse=lse)
-        binding.fa_bwd(q, k, v, o, lse, do, scale, causal, dq=dq, dk=dk, dv=dv, workspace=ws)
+        if noalloc:
+            binding.fa_bwd_noalloc(q, k, v, o, lse, do, scale, causal, dq, dk, dv)
+        else:
+            binding.fa_bwd(q, k, v, o, lse, do, scale, causal, dq=dq, dk=dk, dv=dv, workspace=ws)
 
     # eager references for the three input sets
     eager = []
