@@ -24,9 +24,13 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 OUT = os.path.join(HERE, "csrc", "_build", "ablate")  # git-ignored, travels to the GPU machine with the tree
-VARIANTS = {"full": [], "no_exponentials": ["-DFA_ABLATE=1"], "no_lds_reads_second_gemm": ["-DFA_ABLATE=2"],
-            "no_second_gemm": ["-DFA_ABLATE=3"], "no_softmax_arithmetic": ["-DFA_ABLATE=4"],
-            "phase_trace": ["-DFA_PHASE_TRACE"]}
+# FA_STAGED_TILE8: the eight-wave tile with register staging, the kernel these switches instrument (the library
+# runs the same block arithmetic in fa_fwd_fp8_async_kernel, whose staging bypasses the registers)
+VARIANTS = {"full": ["-DFA_STAGED_TILE8"], "no_exponentials": ["-DFA_STAGED_TILE8", "-DFA_ABLATE=1"],
+            "no_lds_reads_second_gemm": ["-DFA_STAGED_TILE8", "-DFA_ABLATE=2"],
+            "no_second_gemm": ["-DFA_STAGED_TILE8", "-DFA_ABLATE=3"],
+            "no_softmax_arithmetic": ["-DFA_STAGED_TILE8", "-DFA_ABLATE=4"],
+            "phase_trace": ["-DFA_STAGED_TILE8", "-DFA_PHASE_TRACE"], "library": []}
 # the bf16 ping-pong kernel (fa_fwd.hip)
 VARIANTS_16 = {"full": [], "no_exponentials": ["-DFA_ABLATE_PP=1"], "no_v_operand_reads": ["-DFA_ABLATE_PP=2"],
                "no_k_operand_reads": ["-DFA_ABLATE_PP=3"], "no_softmax_arithmetic": ["-DFA_ABLATE_PP=4"]}

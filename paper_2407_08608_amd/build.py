@@ -30,7 +30,7 @@ def _compile(src):
 
 # Sources with MFMAs written as inline assembly: their device assembly is generated once more as
 # text and checked for instructions that touch an MFMA result too early (mfma_hazard_check.py).
-HAZARD_CHECKED = ["fa_bwd.hip", "fa_fwd.hip", "fa_fwd_fp8.hip"]
+HAZARD_CHECKED = ["fa_bwd.hip", "fa_fwd.hip"]
 
 
 def _check_hazards(name):

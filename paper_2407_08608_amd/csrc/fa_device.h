@@ -97,31 +97,6 @@ static __device__ __forceinline__ void mfma_result_wait(f32x16& x, f32x16& y) {
 }
 static __device__ __forceinline__ void mfma_result_wait(f32x16& x) { asm volatile("s_nop 12" : "+v"(x)); }
 
-// The e4m3 MFMA (32x32x64, 16 passes) with the accumulator in ordinary registers; `unit` holds the
-// scale exponents 127 = 1.0 for both operands.  Its result needs 19 wait states before a VALU read.
-struct MfmaFp8VgprAcc {
-    static __device__ __forceinline__ void run(f32x16& acc, const i32x8& a, const i32x8& b, int unit) {
-        asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, %0, %3, %3 op_sel_hi:[0,0,0]"
-                     : "+v"(acc) : "v"(a), "a"(b), "v"(unit));
-    }
-    static __device__ __forceinline__ void first(f32x16& acc, const i32x8& a, const i32x8& b, int unit) {
-        asm volatile("v_mfma_scale_f32_32x32x64_f8f6f4 %0, %1, %2, 0, %3, %3 op_sel_hi:[0,0,0]"
-                     : "=&v"(acc) : "v"(a), "a"(b), "v"(unit));
-    }
-};
-static __device__ __forceinline__ void mfma_fp8_result_wait(f32x16& x, f32x16& y) {
-    asm volatile("s_nop 15\n\ts_nop 4" : "+v"(x), "+v"(y));
-}
-
-// Workgroup barrier for LDS traffic only: waits for this wave's LDS accesses, not for its global loads
-// (__syncthreads() waits for both, which would expose the latency of staging loads that are meant to
-// stay in flight across the barrier; their destination registers are waited for where they are used).
-static __device__ __forceinline__ void lds_barrier() {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 // 32-bit LDS byte address of a __shared__ object, and loads through such an address: a base kept
 // in one register with compile-time offsets lets every read use the instruction's immediate
 // offset field instead of an address computation of its own.
