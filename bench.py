@@ -30,8 +30,8 @@ PEAK_HBM_BYTES_PER_S = 8.0e12  # published HBM3E bandwidth
 # that is renamed or re-tiled no longer matches and its traffic is reported as null until it is measured
 # again.  Source: profiles/fa_fwd_d128_hbm_traffic.txt.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>": 2.967e8,
-    "fa_fwd_fp8_async_kernel<128, 128, false, true>": 1.909e8,
+    "fa_fwd_pingpong_kernel<bf16_tag, 64, 4, false>": 2.966e8,
+    "fa_fwd_fp8_async_kernel<128, 128, false, true>": 1.824e8,
 }
 
 
