@@ -65,7 +65,7 @@ fa_bwd_dkdv_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ 
               const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
               uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, int N,
               int n_kblocks, int total_wg, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int BK = 128;        // keys per workgroup
     constexpr int BQ = 64;         // queries per loop iteration
     constexpr int NT = 256;
@@ -451,7 +451,7 @@ __global__ void __launch_bounds__(NW * 64, NW == 8 ? 2 : 1)
 fa_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                  const uint16_t* __restrict__ dout, const float* __restrict__ lse, const float* __restrict__ dvec,
                  uint16_t* __restrict__ dq, int N, int n_qtiles, int total_wg, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
     constexpr int RSTR = bwd_row_stride(D);  // K tile: row reads and transposed reads

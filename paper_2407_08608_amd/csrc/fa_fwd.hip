@@ -60,7 +60,7 @@ __global__ void __launch_bounds__(NW * 64, (D == 64 && NW == 8) ? 4 : (RQ == 1 &
 fa_fwd_16bit_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                     const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
                     int N, int n_qtiles, int total_wg, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32 * RQ;
     constexpr int KSTR = D + 8;   // +16 B per row: 128-bit row reads hit distinct banks
@@ -305,7 +305,7 @@ __global__ void __launch_bounds__(256, 1)
 fa_fwd_d256_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                    uint16_t* __restrict__ o, float* __restrict__ lse, int N, int n_qtiles, int total_wg,
                    int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int D = 256, BC = 64, NT = 256, BR = 128;
     constexpr int KSTR = D + 8;   // +16 B per row: 128-bit row reads hit distinct banks
     constexpr int VSTR = D + 32;  // +64 B per row: the 4-row transposing reads hit distinct banks
@@ -589,7 +589,7 @@ __global__ void __launch_bounds__(512, 2)
 fa_fwd_pingpong_kernel(const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
                        const uint16_t* __restrict__ v, uint16_t* __restrict__ o, float* __restrict__ lse,
                        int N, int n_qtiles, int total_wg, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int D = 128;
     constexpr int BR = 256;
     constexpr int NS = 4;              // LDS stages per tensor

@@ -63,7 +63,7 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
                   const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                   const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
                   int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int NT = NW * 64;
     constexpr int BR = NW * 32;
     constexpr int KSTR = D + 16;  // bytes per LDS row
@@ -342,7 +342,7 @@ fa_fwd_fp8_async_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict
                          const float* __restrict__ q_scale, const float* __restrict__ k_scale,
                          const float* __restrict__ v_scale, uint16_t* __restrict__ o, float* __restrict__ lse, int N,
                          int n_qtiles, int total_wg, int n_sblocks, int kv_group, float scale) {
-    ClockSpan clock_span;  // measurement builds only; empty otherwise
+    [[maybe_unused]] ClockSpan clock_span;  // measurement builds only; empty otherwise
     constexpr int NW = 8, BR = NW * 32;
     constexpr int NS = 2;            // LDS stages per tensor
     static_assert((D == 256 && BC == 64) || (D == 128 && BC == 128) || (D == 64 && BC == 128),
