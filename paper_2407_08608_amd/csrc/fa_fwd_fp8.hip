@@ -327,8 +327,9 @@ fa_fwd_fp8_kernel(const uint8_t* __restrict__ q, const uint8_t* __restrict__ k, 
 }
 
 // ---------------------------------------------------------------------------------------
-// Eight waves (two per SIMD), 256 queries per tile, 16 KiB key blocks (64 keys at d = 256, 128 at d = 128):
-// the lock-step tile of fa_fwd_fp8_kernel with the staging taken out of the registers.  K and V blocks go
+// Eight waves (two per SIMD), 256 queries per tile, key blocks of 16 KiB (64 keys at d = 256, 128 at d = 128)
+// or 8 KiB (128 keys at d = 64): the lock-step tile of fa_fwd_fp8_kernel with the staging taken out of the
+// registers.  K and V blocks go
 // from global memory straight into two LDS stages per tensor (buffer loads with an LDS destination, one
 // block ahead), as unpadded rows whose 16-byte chunk index is XOR-swizzled through the global address a
 // lane fetches; both read patterns are free of bank conflicts.  At d = 256 this is what makes two waves
