@@ -80,7 +80,7 @@ def main():
                     help="for rocprofv3 --pmc runs: a plain 256 MiB device copy (calibration) followed by the "
                          "six non-causal bf16 and the six non-causal FP8 forward launches, three times each; "
                          "prints nothing")
-    ap.add_argument("--counter-probe", choices=("bwd", "fp8", "sched4", "sched8", "schedpp"),
+    ap.add_argument("--counter-probe", choices=("bwd", "fp8", "fp8_d64", "fp8_d256", "sched4", "sched8", "schedpp"),
                     help="for rocprofv3 --pmc runs: three launches of the bf16 backward (bwd) or of the block-scaled "
                          "FP8 forward (fp8) at seqlen 16k, d = 128, non-causal, or of one forced schedule of the "
                          "fp16 forward at the ablation shape (batch 4, seqlen 8448); prints nothing")
@@ -332,7 +332,7 @@ def counter_probe(torch, binding, inputs, dev, which):
             binding.fa_fwd_schedule(q, k, v, d ** -0.5, False, sched)
         torch.cuda.synchronize()
         return
-    N, d = 16384, 128
+    N, d = 16384, {"fp8_d64": 64, "fp8_d256": 256}.get(which, 128)
     B, H = inputs.benchmark_shape(N, d)
     q, k, v = (t.to(dev) for t in inputs.qkv(7, B, H, N, d, "bf16"))
     if which == "bwd":
