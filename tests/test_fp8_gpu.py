@@ -172,11 +172,12 @@ def test_fp8_row_maxima_that_rise_block_after_block(N, d, causal):
 
 
 @pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("N", [333, 1500])
 @pytest.mark.parametrize("d", [64, 128, 256])
-def test_fp8_unit_scale_entry_point_matches_oracle(d, causal):
-    """fa_fwd with dtype e4m3 takes the codes at unit scale: every head dimension has an instantiation
-    without block scales of its own."""
-    B, H, N = 1, 2, 333
+def test_fp8_unit_scale_entry_point_matches_oracle(d, N, causal):
+    """fa_fwd with dtype e4m3 takes the codes at unit scale: every kernel (the four-wave tiles at 333 keys, the
+    eight-wave tiles at 1500) has an instantiation without block scales of its own."""
+    B, H = 1, 2
     rng = np.random.default_rng(43 + d)
     qc, kc, vc = (f8.e4m3_encode(rng.standard_normal((B, H, N, d))) for _ in range(3))
     dev = [torch.from_numpy(c).cuda() for c in (qc, kc, vc)]
